@@ -1,0 +1,421 @@
+"""Pins for the CPU oracle: it is checked against what the paper's definitions and plain
+mathematics fix (closed forms, dense brute force on tiny graphs, the paper's worked halo
+example, finite differences), never against itself or against the GPU path."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------- helpers
+def rand_edges(n, m, seed, directed=False):
+    rng = np.random.default_rng(seed)
+    u = rng.integers(0, n, m)
+    v = rng.integers(0, n, m)
+    if directed:
+        return u.astype(np.int32), v.astype(np.int32)
+    return np.concatenate([u, v]).astype(np.int32), np.concatenate([v, u]).astype(np.int32)
+
+
+def dense_norm_adj(src, dst, n):
+    """Sec. 3.1 written out densely in fp64: A^ = D^-1/2 (A + I) D^-1/2, D = row sums of A + I."""
+    A = np.zeros((n, n))
+    for s, t in zip(src, dst):
+        if s != t:
+            A[s, t] = 1.0
+    At = A + np.eye(n)
+    d = At.sum(axis=1)
+    return At / np.sqrt(np.outer(d, d)), d, At
+
+
+def csr_to_dense(g, vals):
+    M = np.zeros((g.nr, g.nc))
+    for i in range(g.nr):
+        for k in range(g.rowptr[i], g.rowptr[i + 1]):
+            assert M[i, g.col[k]] == 0.0, "duplicate column in a row"
+            M[i, g.col[k]] = vals[k]
+    return M
+
+
+def ulp_diff(a, b):
+    a = np.asarray(a, np.float32).view(np.int32).astype(np.int64)
+    b = np.asarray(b, np.float32).view(np.int32).astype(np.int64)
+    return np.abs(a - b)
+
+
+# ----------------------------------------------------------------------------- A^ values
+@pytest.mark.parametrize("seed,directed", [(1, False), (2, False), (3, True)])
+def test_adjacency_matches_dense_definition(seed, directed):
+    n = 97
+    src, dst = rand_edges(n, 600, seed, directed)
+    g = oracle.graph_build(src, dst, n)
+    Ad, d, At = dense_norm_adj(src, dst, n)
+    # pattern, degrees, fp64 values, fp32 values
+    assert np.array_equal(csr_to_dense(g, np.ones(g.nnz)), At)
+    assert np.array_equal(g.deg, d.astype(np.int32))
+    assert g.nnz == int(At.sum()) == int(g.deg.sum())
+    np.testing.assert_allclose(csr_to_dense(g, g.val64), Ad, rtol=1e-15, atol=0)
+    assert ulp_diff(csr_to_dense(g, g.val), Ad.astype(np.float32)).max() <= 2
+    # columns strictly ascending inside every row
+    for i in range(n):
+        c = g.col[g.rowptr[i]:g.rowptr[i + 1]]
+        assert np.all(np.diff(c) > 0)
+
+
+def test_closed_forms_ring_complete_star():
+    # k-regular ring: every value 1/(k+1), every row sum 1
+    n, k = 64, 6
+    s = np.repeat(np.arange(n), k)
+    t = (s + np.tile(np.concatenate([np.arange(1, k // 2 + 1), -np.arange(1, k // 2 + 1)]), n)) % n
+    g = oracle.graph_build(s, t, n)
+    assert np.all(g.deg == k + 1)
+    np.testing.assert_allclose(g.val64, 1.0 / (k + 1), rtol=1e-15)
+    # complete graph: A^ = (1/n) 1 1^T so A^ X = column means
+    n = 23
+    s, t = np.nonzero(~np.eye(n, dtype=bool))
+    g = oracle.graph_build(s, t, n)
+    X = np.random.default_rng(0).standard_normal((n, 5)).astype(np.float32)
+    Y, _ = oracle.spmm(g.rowptr, g.col, g.val, X)
+    np.testing.assert_allclose(Y, np.tile(X.astype(np.float64).mean(0), (n, 1)), rtol=1e-6, atol=1e-7)
+    # star: centre degree n (n-1 leaves + itself), leaves degree 2
+    n = 50
+    leaves = np.arange(1, n)
+    s = np.concatenate([np.zeros(n - 1, int), leaves]); t = np.concatenate([leaves, np.zeros(n - 1, int)])
+    g = oracle.graph_build(s, t, n)
+    assert g.deg[0] == n and np.all(g.deg[1:] == 2)
+    row0 = g.val64[g.rowptr[0]:g.rowptr[1]]
+    np.testing.assert_allclose(row0[0], 1.0 / n, rtol=1e-15)           # diagonal 1/d_0
+    np.testing.assert_allclose(row0[1:], 1.0 / np.sqrt(2.0 * n), rtol=1e-15)
+
+
+def test_sqrt_degree_is_fixed_vector(c1):
+    # sum_j A^(i,j) sqrt(d_j) = sum_{j in N(i)+i} 1/sqrt(d_i) = sqrt(d_i)
+    g = oracle.graph_build(c1["src"], c1["dst"], c1["n"])
+    sd = np.sqrt(g.deg.astype(np.float64))
+    r64 = np.add.reduceat(g.val64 * sd[g.col], g.rowptr[:-1])
+    np.testing.assert_allclose(r64, sd, rtol=1e-13)
+    Y, _ = oracle.spmm(g.rowptr, g.col, g.val, sd.astype(np.float32)[:, None])
+    np.testing.assert_allclose(Y[:, 0], sd, rtol=5e-7)
+    # diagonal entries are 1/d_i; symmetric graph => symmetric A^
+    diag = np.array([g.val64[g.rowptr[i]:g.rowptr[i + 1]][g.col[g.rowptr[i]:g.rowptr[i + 1]] == i][0]
+                     for i in range(0, g.nr, 37)])
+    np.testing.assert_allclose(diag, 1.0 / g.deg[::37], rtol=1e-15)
+
+
+# ----------------------------------------------------------------------------- CSC
+def test_csc_of_symmetric_equals_csr_bitwise(c1):
+    g = oracle.graph_build(c1["src"], c1["dst"], c1["n"])
+    assert np.array_equal(g.colptr, g.rowptr)
+    assert np.array_equal(g.rowidx, g.col)
+    assert np.array_equal(g.val_t.view(np.int32), g.val.view(np.int32))
+
+
+def test_csc_of_directed_is_dense_transpose():
+    n = 61
+    src, dst = rand_edges(n, 400, 7, directed=True)
+    g = oracle.graph_build(src, dst, n)
+    M = csr_to_dense(g, g.val)
+    Mt = np.zeros((n, n), np.float32)
+    for j in range(n):
+        r = g.rowidx[g.colptr[j]:g.colptr[j + 1]]
+        assert np.all(np.diff(r) > 0)
+        Mt[j, r] = g.val_t[g.colptr[j]:g.colptr[j + 1]]
+    assert np.array_equal(Mt, M.T.astype(np.float32))
+    assert not np.array_equal(M, M.T)           # the case really is asymmetric
+
+
+# ----------------------------------------------------------------------------- halo list
+def _read_golden():
+    facts = {}
+    for line in open(os.path.join(GOLDEN, "halo_example.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        k, *rest = line.split()
+        facts[k] = rest
+    return facts
+
+
+def test_halo_list_paper_worked_example():
+    f = _read_golden()
+    e = np.array([[int(x) for x in p.split("-")] for p in f["edges"]]) - 1     # 0-based
+    src = np.concatenate([e[:, 0], e[:, 1]]); dst = np.concatenate([e[:, 1], e[:, 0]])
+    n = 6
+    whole = oracle.graph_build(src, dst, n)
+    blk = [int(x) - 1 for x in f["block"][0].split(",")]
+    g = oracle.graph_build(src, dst, n, blk[0], blk[-1] + 1, deg_global=whole.deg)
+    want = [int(x) - 1 for x in f["halo"][0].split(",")]
+    assert g.halo_gid.tolist() == want and g.nh == 3
+    parts = [[int(x) - 1 for x in p.split(",")] for p in f["parts"]]
+    from_p1 = [h for h in g.halo_gid if h in parts[0]]
+    from_p2 = [h for h in g.halo_gid if h in parts[1]]
+    assert from_p1 == [int(x) - 1 for x in f["halo_from_p1"][0].split(",")]
+    assert from_p2 == [int(x) - 1 for x in f["halo_from_p2"][0].split(",")]
+    assert len(set(g.halo_gid.tolist())) == g.nh                 # row 4 listed once
+    assert whole.deg[0] == int(f["row_weight_v1"][0])
+    col2_rows = sorted(whole.rowidx[whole.colptr[1]:whole.colptr[2]] + 1)
+    assert col2_rows == [int(x) for x in f["col2_rows"][0].split(",")]
+    col4 = sorted(set(whole.rowidx[whole.colptr[3]:whole.colptr[4]] + 1) - {4})
+    assert col4 == [int(x) for x in f["col4_offdiag_rows"][0].split(",")]
+    # v5 (local row 0) reads owned v5 then halo slots of v1, v4; v6 reads v6 then v2, v4
+    assert g.col[g.rowptr[0]:g.rowptr[1]].tolist() == [0, 2 + 0, 2 + 2]
+    assert g.col[g.rowptr[1]:g.rowptr[2]].tolist() == [1, 2 + 1, 2 + 2]
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_halo_list_brute_force_and_partition_invariance(seed):
+    rng = np.random.default_rng(seed)
+    n = 120
+    src, dst = rand_edges(n, 700, seed, directed=(seed == 13))
+    whole = oracle.graph_build(src, dst, n)
+    X = rng.standard_normal((n, 7)).astype(np.float32)
+    Yw, _ = oracle.spmm(whole.rowptr, whole.col, whole.val, X)
+    cuts = [0, 31, 32, 90, n]
+    for lo, hi in zip(cuts[:-1], cuts[1:]):
+        g = oracle.graph_build(src, dst, n, lo, hi, deg_global=whole.deg)
+        cols = set()
+        for s, t in zip(src, dst):
+            if lo <= s < hi and s != t and not (lo <= t < hi):
+                cols.add(int(t))
+        assert g.halo_gid.tolist() == sorted(cols)
+        assert np.array_equal(g.deg, whole.deg[lo:hi])
+        # block form (Sec. 4.1, second equation): owned rows + received rows give the rows of A X
+        Xb = np.concatenate([X[lo:hi], X[g.halo_gid]])
+        Yb, _ = oracle.spmm(g.rowptr, g.col, g.val, Xb)
+        np.testing.assert_allclose(Yb, Yw[lo:hi], rtol=1e-12, atol=1e-13)
+        # each row: owned columns first (ascending), then halo slots (ascending)
+        for i in range(g.nr):
+            assert np.all(np.diff(g.col[g.rowptr[i]:g.rowptr[i + 1]]) > 0)
+
+
+def test_graph_build_rejects_bad_input():
+    with pytest.raises(ValueError):
+        oracle.graph_build([0, 5], [1, 2], 4)
+    with pytest.raises(ValueError):
+        oracle.graph_build([0, 1], [1, 0], 4, 0, 2)          # block without global degrees
+
+
+def test_duplicates_and_self_loops_collapse():
+    src = [0, 0, 0, 1, 2, 2, 2]; dst = [1, 1, 0, 0, 2, 0, 0]
+    g = oracle.graph_build(src, dst, 3)
+    assert g.rowptr.tolist() == [0, 2, 4, 6]
+    assert g.col.tolist() == [0, 1, 0, 1, 0, 2]
+    assert g.deg.tolist() == [2, 2, 2]
+
+
+# ----------------------------------------------------------------------------- SpMM
+def test_spmm_against_dense_and_adjoint():
+    n = 83
+    src, dst = rand_edges(n, 500, 21, directed=True)
+    g = oracle.graph_build(src, dst, n)
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((n, 9)).astype(np.float32)
+    Yv = rng.standard_normal((n, 9)).astype(np.float32)
+    M = csr_to_dense(g, g.val.astype(np.float64))
+    Y, B = oracle.spmm(g.rowptr, g.col, g.val, X)
+    np.testing.assert_allclose(Y, M @ X.astype(np.float64), rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(B, np.abs(M) @ np.abs(X.astype(np.float64)), rtol=1e-13)
+    Yt, _ = oracle.spmm(g.colptr, g.rowidx, g.val_t, Yv)
+    np.testing.assert_allclose(Yt, M.T @ Yv.astype(np.float64), rtol=1e-13, atol=1e-14)
+    # <Yv, A X> = <A^T Yv, X>
+    np.testing.assert_allclose((Yv.astype(np.float64) * Y).sum(), (Yt * X.astype(np.float64)).sum(), rtol=1e-11)
+    # row subset
+    rows = np.array([5, 0, 82, 5])
+    Ys, _ = oracle.spmm(g.rowptr, g.col, g.val, X, rows=rows)
+    np.testing.assert_array_equal(Ys, Y[rows])
+
+
+# ----------------------------------------------------------------------------- dense products
+def test_gemm_forms():
+    rng = np.random.default_rng(3)
+    A = rng.standard_normal((13, 7)).astype(np.float32)
+    B = rng.standard_normal((7, 5)).astype(np.float32)
+    A64, B64 = A.astype(np.float64), B.astype(np.float64)
+    C, Bd = oracle.gemm("nn", A, B)
+    np.testing.assert_allclose(C, A64 @ B64, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(Bd, np.abs(A64) @ np.abs(B64), rtol=1e-13)
+    C, _ = oracle.gemm("nt", A, B.T.copy())
+    np.testing.assert_allclose(C, A64 @ B64, rtol=1e-13, atol=1e-14)
+    C, _ = oracle.gemm("tn", A.T.copy(), B)
+    np.testing.assert_allclose(C, A64 @ B64, rtol=1e-13, atol=1e-14)
+    # identity and one-hot weights
+    C, _ = oracle.gemm("nn", A, np.eye(7, dtype=np.float32))
+    np.testing.assert_array_equal(C, A64)
+    sel = np.zeros((7, 2), np.float32); sel[3, 0] = 1; sel[6, 1] = 1
+    C, _ = oracle.gemm("nn", A, sel)
+    np.testing.assert_array_equal(C, A64[:, [3, 6]])
+    # a non-square transposed case cannot be confused with the plain one
+    C, _ = oracle.gemm("tn", A, rng.standard_normal((13, 4)).astype(np.float32))
+    assert C.shape == (7, 4)
+
+
+# ----------------------------------------------------------------------------- softmax cross-entropy
+def test_softmax_xent_closed_forms():
+    nr, C = 37, 8
+    y = (np.arange(nr) % C).astype(np.int32)
+    scale = 1.0 / nr
+    loss, labs, G = oracle.softmax_xent(np.zeros((nr, C), np.float32), y, scale)
+    np.testing.assert_allclose(loss, np.log(C), rtol=1e-14)
+    np.testing.assert_allclose(labs, np.log(C), rtol=1e-14)
+    want = np.full((nr, C), scale / C); want[np.arange(nr), y] -= scale
+    np.testing.assert_allclose(G, want, rtol=1e-14)
+    rng = np.random.default_rng(9)
+    Z = (3 * rng.standard_normal((nr, C))).astype(np.float32)
+    l1, _, G1 = oracle.softmax_xent(Z, y, scale)
+    np.testing.assert_allclose(G1.sum(1), 0.0, atol=1e-16)
+    l2, _, G2 = oracle.softmax_xent(Z + np.float32(4.0), y, scale)      # shift invariance
+    np.testing.assert_allclose(l2, l1, rtol=1e-6); np.testing.assert_allclose(G2, G1, atol=1e-7)
+    # unlabeled rows
+    y2 = y.copy(); y2[::3] = -1
+    l3, _, G3 = oracle.softmax_xent(Z, y2, scale)
+    assert np.all(G3[::3] == 0) and np.array_equal(G3[1::3], G1[1::3]) and l3 < l1
+    # direct formula in numpy fp64
+    Zd = Z.astype(np.float64)
+    lse = np.log(np.exp(Zd).sum(1))
+    np.testing.assert_allclose(l1, scale * (lse - Zd[np.arange(nr), y]).sum(), rtol=1e-13)
+
+
+def test_softmax_xent_finite_differences():
+    nr, C = 9, 5
+    rng = np.random.default_rng(4)
+    Z = rng.standard_normal((nr, C)).astype(np.float32)
+    y = rng.integers(0, C, nr).astype(np.int32)
+    _, _, G = oracle.softmax_xent(Z, y, 0.7)
+
+    def J(Zd):
+        return 0.7 * (np.log(np.exp(Zd).sum(1)) - Zd[np.arange(nr), y]).sum()
+    Zd = Z.astype(np.float64); h = 1e-6
+    for i in range(nr):
+        for c in range(C):
+            E = np.zeros_like(Zd); E[i, c] = h
+            fd = (J(Zd + E) - J(Zd - E)) / (2 * h)
+            assert abs(fd - G[i, c]) <= 1e-8 + 1e-6 * abs(fd)
+
+
+# ----------------------------------------------------------------------------- layer forward / backward
+def _dense_two_layer(Ad, X, W1, W2, y, scale):
+    """Independent fp64 forward pass written with dense numpy (Sec. 3.1, first equation, twice)."""
+    Z1 = Ad @ X @ W1
+    H1 = np.maximum(Z1, 0.0)
+    Z2 = Ad @ H1 @ W2
+    lse = np.log(np.exp(Z2 - Z2.max(1, keepdims=True)).sum(1)) + Z2.max(1)
+    return scale * (lse - Z2[np.arange(len(y)), y]).sum(), Z1, H1, Z2
+
+
+@pytest.mark.parametrize("directed", [False, True])
+def test_layer_formulas_by_finite_differences(directed):
+    n, d0, d1, d2 = 40, 6, 5, 4
+    src, dst = rand_edges(n, 160, 31, directed)
+    g = oracle.graph_build(src, dst, n)
+    Ad = csr_to_dense(g, g.val.astype(np.float64))
+    rng = np.random.default_rng(8)
+    X = rng.standard_normal((n, d0)).astype(np.float32)
+    W1 = (0.5 * rng.standard_normal((d0, d1))).astype(np.float32)
+    W2 = (0.5 * rng.standard_normal((d1, d2))).astype(np.float32)
+    y = rng.integers(0, d2, n).astype(np.int32)
+    scale = 1.0 / n
+    J0, Z1d, H1d, Z2d = _dense_two_layer(Ad, X.astype(np.float64), W1.astype(np.float64), W2.astype(np.float64), y, scale)
+
+    # oracle forward (fp64 outputs), layer by layer on the exact fp64 chain where possible
+    f1 = oracle.layer_fwd(g, X, W1, act="relu")
+    np.testing.assert_allclose(f1["Z"], Z1d, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(f1["Hout"], H1d, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(f1["AH"], Ad @ X.astype(np.float64), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(f1["Bz"], np.abs(Ad) @ np.abs(X.astype(np.float64)) @ np.abs(W1.astype(np.float64)), rtol=1e-12)
+    # the other association gives the same numbers
+    P, _ = oracle.gemm("nn", X, W1)
+    np.testing.assert_allclose(Ad @ P, f1["Z"], rtol=1e-12, atol=1e-13)
+
+    # To finite-difference the whole chain the fp32 hand-over between layers must not round:
+    # use fp32-representable H1 by recomputing the dense chain from the rounded values.
+    H1 = f1["Hout"].astype(np.float32)
+    Z1 = f1["Z"].astype(np.float32)
+    f2 = oracle.layer_fwd(g, H1, W2, act="none")
+    loss, _, G2 = oracle.softmax_xent(f2["Z"].astype(np.float32), y, scale)
+    b2 = oracle.layer_bwd(g, H1, W2, G2.astype(np.float32), Zprev=Z1, want_dH=True, want_dbias=True)
+    G1 = b2["dH"].astype(np.float32)
+    b1 = oracle.layer_bwd(g, X, W1, G1, Zprev=None, want_dH=True)
+
+    # central differences on the dense fp64 model, entries near a ReLU kink excluded
+    h = 1e-6
+    X64, W164, W264 = X.astype(np.float64), W1.astype(np.float64), W2.astype(np.float64)
+
+    def Jof(Xp=X64, W1p=W164, W2p=W264):
+        return _dense_two_layer(Ad, Xp, W1p, W2p, y, scale)[0]
+    assert np.abs(Z1d).min() > 1e-4
+    tol = lambda fd: 2e-6 * abs(fd) + 2e-8     # fp32 hand-overs between the layer calls
+    for k in range(d1):
+        for c in range(d2):
+            E = np.zeros_like(W264); E[k, c] = h
+            fd = (Jof(W2p=W264 + E) - Jof(W2p=W264 - E)) / (2 * h)
+            assert abs(fd - b2["dW"][k, c]) <= tol(fd), ("dW2", k, c, fd, b2["dW"][k, c])
+    for k in range(d0):
+        for c in range(d1):
+            E = np.zeros_like(W164); E[k, c] = h
+            fd = (Jof(W1p=W164 + E) - Jof(W1p=W164 - E)) / (2 * h)
+            assert abs(fd - b1["dW"][k, c]) <= tol(fd), ("dW1", k, c, fd, b1["dW"][k, c])
+    for j in range(0, n, 3):
+        for k in range(d0):
+            E = np.zeros_like(X64); E[j, k] = h
+            fd = (Jof(Xp=X64 + E) - Jof(Xp=X64 - E)) / (2 * h)
+            assert abs(fd - b1["dH"][j, k]) <= tol(fd), ("dX", j, k, fd, b1["dH"][j, k])
+    # dbias = column sums of G
+    np.testing.assert_allclose(b2["dbias"], G2.astype(np.float32).astype(np.float64).sum(0), rtol=1e-12, atol=1e-15)
+    # mask really applied: dH of layer 2 is zero exactly where Z1 <= 0
+    assert np.all(b2["dH"][Z1 <= 0] == 0.0) and np.any(Z1 <= 0) and np.any(b2["dH"] != 0)
+
+
+def test_layer_backward_on_blocks_sums_to_whole():
+    """Sec. 4.2: the per-processor dW_m add up to dW; dH rows (owned + pushed halo parts) add up to S."""
+    n, d_in, d_out = 90, 5, 3
+    src, dst = rand_edges(n, 420, 41, directed=True)
+    whole = oracle.graph_build(src, dst, n)
+    rng = np.random.default_rng(2)
+    H = rng.standard_normal((n, d_in)).astype(np.float32)
+    W = rng.standard_normal((d_in, d_out)).astype(np.float32)
+    G = rng.standard_normal((n, d_out)).astype(np.float32)
+    bw = oracle.layer_bwd(whole, H, W, G, Zprev=None)
+    dW = np.zeros((d_in, d_out)); S = np.zeros((n, d_in))
+    Zw = oracle.layer_fwd(whole, H, W, act="none")["Z"]
+    for lo, hi in [(0, 30), (30, 31), (31, 90)]:
+        g = oracle.graph_build(src, dst, n, lo, hi, deg_global=whole.deg)
+        Hb = np.concatenate([H[lo:hi], H[g.halo_gid]])
+        b = oracle.layer_bwd(g, Hb, W, G[lo:hi], Zprev=None)
+        dW += b["dW"]
+        S[lo:hi] += b["dH"][: g.nr]
+        S[g.halo_gid] += b["dH"][g.nr:]
+        np.testing.assert_allclose(oracle.layer_fwd(g, Hb, W, act="none")["Z"], Zw[lo:hi], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(dW, bw["dW"], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(S, bw["dH"], rtol=1e-11, atol=1e-12)
+
+
+def test_bias_and_identity_activation():
+    n = 30
+    src, dst = rand_edges(n, 100, 51)
+    g = oracle.graph_build(src, dst, n)
+    rng = np.random.default_rng(1)
+    H = rng.standard_normal((n, 4)).astype(np.float32)
+    W = rng.standard_normal((4, 3)).astype(np.float32)
+    b = rng.standard_normal(3).astype(np.float32)
+    f0 = oracle.layer_fwd(g, H, W, act="none")
+    f1 = oracle.layer_fwd(g, H, W, bias=b, act="none")
+    np.testing.assert_allclose(f1["Z"] - f0["Z"], np.tile(b.astype(np.float64), (n, 1)), atol=1e-14)
+    assert np.array_equal(f0["Z"], f0["Hout"])
+    fr = oracle.layer_fwd(g, H, W, act="relu")
+    assert np.array_equal(fr["Hout"], np.maximum(fr["Z"], 0.0)) and np.any(fr["Z"] < 0)
+
+
+# ----------------------------------------------------------------------------- gather
+def test_gather_identity_and_round_trip():
+    rng = np.random.default_rng(6)
+    T = rng.standard_normal((50, 6)).astype(np.float32)
+    assert np.array_equal(oracle.gather(T, np.arange(50)), T)
+    p = rng.permutation(50); inv = np.argsort(p)
+    assert np.array_equal(oracle.gather(oracle.gather(T, p), inv), T)
+    assert np.array_equal(oracle.gather(T, [3, 3, 49]), T[[3, 3, 49]])
+    with pytest.raises(ValueError):
+        oracle.gather(T, [50])
