@@ -1,0 +1,188 @@
+/*
+ * gcn.h -- C ABI of the MI355X (gfx950) GCN layer library.
+ *
+ * One full-batch GCN layer on one GPU's row block of a 1D row-partitioned graph
+ * ("Scalable Graph Convolutional Network Training on Distributed-Memory Systems",
+ * Sec. 3.1 graph convolution, Sec. 4.1 feedforward, Sec. 4.2 backpropagation):
+ *
+ *     forward   Z = A^ H W,  Hout = act(Z)                       (Sec. 3.1, first equation)
+ *     backward  dW = (A^ H)^T G,  dH = (A^T G W^T) (.) [Zprev>0] (Sec. 3.1, 2nd/3rd equations;
+ *                                                                 A^T for directed graphs)
+ *
+ * with A^ = D^-1/2 (A + I) D^-1/2 stored in CSR (and CSC for the transpose).  A block owns
+ * nr consecutive global rows [row_lo, row_hi); the nh distinct non-owned columns it touches
+ * ("halo", Sec. 4.1: the rows received from other processors, each one once) are numbered
+ * nr .. nr+nh-1 in ascending global id.  Dense operands of a block therefore have
+ * nc = nr + nh rows: owned rows first, then halo rows in halo-list order.
+ *
+ * General conventions
+ *  - Every function returns 0 (GCN_OK) or a negative error code; gcn_last_error() gives a
+ *    thread-local message for the last failure.  Nothing aborts, throws or prints.
+ *  - All dense buffers are caller-owned DEVICE pointers (gcn_halo_gather's table may also be
+ *    pinned host memory), row-major, with the leading dimension given in elements.  The
+ *    library never frees or keeps them.
+ *  - gcn_csr_t is an opaque, library-owned handle (device arrays + a scratch workspace that
+ *    grows on demand and is reused by later calls).  Calls that use the same handle must not
+ *    overlap in time.
+ *  - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls only enqueue
+ *    work; they do not synchronise, except gcn_csr_build (it must learn nnz and nh) and a
+ *    call that has to grow the handle's workspace.
+ *  - Indices are int32, row/column pointers int64, matrix values and all accumulators fp32.
+ *    dtype selects the element type of *feature* buffers: GCN_F32, or GCN_BF16 (bf16 storage,
+ *    fp32 accumulation, round-to-nearest-even on store).
+ */
+#ifndef GCN_H_
+#define GCN_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GCN_OK 0
+#define GCN_EINVAL (-1) /* bad argument: null pointer, negative size, ld < d, id out of range ... */
+#define GCN_ENOMEM (-2) /* device allocation failed */
+#define GCN_EHIP (-3)   /* HIP runtime error */
+
+#define GCN_F32 0
+#define GCN_BF16 1
+
+#define GCN_BUILD_CSC 1 /* also build the column-major copy needed by gcn_spmm_t / gcn_layer_bwd */
+
+#define GCN_EPI_NONE 0 /* Y = A X (+ bias) */
+#define GCN_EPI_RELU 1 /* Y = max(A X (+ bias), 0) */
+#define GCN_EPI_MASK 2 /* Y = (A X) * [Zprev > 0]   (ReLU derivative: 1 for z > 0, else 0) */
+
+#define GCN_ACT_NONE 0
+#define GCN_ACT_RELU 1
+
+typedef struct gcn_csr gcn_csr_t;
+
+/* Message of the last error raised on the calling thread ("" if none). */
+const char* gcn_last_error(void);
+
+/*
+ * Build the normalised adjacency block (Sec. 3.1: A^ = D^-1/2 (A+I) D^-1/2, D(i,i) = row sum
+ * of A+I; Sec. 4.1: halo rows = cols(A_m) not owned by m, each listed once).
+ *
+ *   d_src, d_dst  device int32[n_edges]: directed edges (row = src, column = dst) in GLOBAL
+ *                 ids.  Duplicates and self-loops are allowed (A is a 0/1 pattern: duplicates
+ *                 collapse, input self-loops are replaced by the single diagonal entry of I).
+ *                 Edges whose src is outside [row_lo, row_hi) are ignored.
+ *   n_global      number of vertices of the whole graph; every id must lie in [0, n_global).
+ *   row_lo,row_hi owned rows; (0, n_global) means the whole graph.
+ *   d_deg_global  device int32[n_global] or NULL: degrees INCLUDING the self-loop of every
+ *                 global vertex.  Required when the block is not the whole graph (the degrees
+ *                 of halo vertices cannot be derived from the block's own rows).
+ *   flags         GCN_BUILD_CSC or 0.
+ *
+ * Result: CSR with columns in local numbering (owned j -> j - row_lo, halo -> nr + rank),
+ * strictly ascending inside each row; val(i,j) = fl(1/sqrt(d_i)) * fl(1/sqrt(d_j)) in fp32;
+ * deg[i] = number of entries of row i.  Synchronises `stream`.  On error *out is NULL.
+ */
+int gcn_csr_build(const int32_t* d_src, const int32_t* d_dst, int64_t n_edges, int64_t n_global,
+                  int64_t row_lo, int64_t row_hi, const int32_t* d_deg_global, int flags,
+                  void* stream, gcn_csr_t** out);
+
+/* Sizes of a block: owned rows, halo rows, stored entries.  Any output pointer may be NULL. */
+int gcn_csr_info(const gcn_csr_t* A, int64_t* nr, int64_t* nh, int64_t* nnz);
+
+/*
+ * Device pointers to the handle's arrays (for inspection / parity checks; owned by the
+ * handle, valid until gcn_csr_free).  Any output pointer may be NULL.  colptr/rowidx/val_t
+ * are NULL if the handle was built without GCN_BUILD_CSC.
+ *   rowptr int64[nr+1], col int32[nnz], val f32[nnz], deg int32[nr], halo_gid int32[nh],
+ *   colptr int64[nc+1], rowidx int32[nnz] (ascending inside each column), val_t f32[nnz].
+ */
+int gcn_csr_arrays(const gcn_csr_t* A, const int64_t** rowptr, const int32_t** col,
+                   const float** val, const int32_t** deg, const int32_t** halo_gid,
+                   const int64_t** colptr, const int32_t** rowidx, const float** val_t);
+
+/* Free the handle, its device arrays and its workspace.  NULL is accepted. */
+int gcn_csr_free(gcn_csr_t* A);
+
+/*
+ * Y[nr x d] = epilogue( A^_m X[nc x d] + bias )          (Sec. 4.1, the sum of the per-row task:
+ *                                                         sum_{j in cols(A(i,:))} A(i,j) X(j,:))
+ *   X, Y      device, element type `dtype`, leading dimensions ldx >= d, ldy >= d.
+ *   epilogue  GCN_EPI_NONE | GCN_EPI_RELU | GCN_EPI_MASK.
+ *   bias      device f32[d] or NULL (added before the activation; not part of the paper's layer).
+ *   Zprev     device [nr x d] (ldz), only read for GCN_EPI_MASK.
+ * X and Y must not alias.  Rows are reduced in a fixed order: results are run-to-run identical.
+ */
+int gcn_spmm(const gcn_csr_t* A, const void* X, int64_t ldx, int d, int dtype, void* Y,
+             int64_t ldy, int epilogue, const float* bias, const void* Zprev, int64_t ldz,
+             void* stream);
+
+/*
+ * Y[nc x d] = epilogue( A^_m^T X[nr x d] )   (Sec. 3.1: for a directed graph backpropagation
+ * uses the transpose).  Needs GCN_BUILD_CSC.  Rows nr..nc-1 of Y are the contributions of
+ * this block to rows owned elsewhere.  GCN_EPI_MASK applies to the owned rows 0..nr-1 only
+ * (Zprev is [nr x d]); halo rows are written unmasked.
+ */
+int gcn_spmm_t(const gcn_csr_t* A, const void* X, int64_t ldx, int d, int dtype, void* Y,
+               int64_t ldy, int epilogue, const void* Zprev, int64_t ldz, void* stream);
+
+/*
+ * recv[s, :] = table[idx[s], :] for s < n_idx   (Sec. 4.1: selecting the rows of H named by an
+ * index set -- the selector-matrix product that copies instead of multiplying -- and filling
+ * the receive buffer of non-local rows).
+ *   table   [n_table_rows x d] (ld), DEVICE memory or PINNED HOST memory mapped into the device.
+ *   d_idx   device int32[n_idx]; every index must lie in [0, n_table_rows).  An out-of-range
+ *           index is never dereferenced: that output row is zero-filled instead.
+ *   recv    device [n_idx x d] (ldr).  Element type `dtype` for both table and recv.
+ */
+int gcn_halo_gather(const void* table, int64_t ld, int64_t n_table_rows, int d, int dtype,
+                    const int32_t* d_idx, int64_t n_idx, void* recv, int64_t ldr, void* stream);
+
+/*
+ * Forward pass of one layer on the block (Sec. 3.1 first equation, Sec. 4.1):
+ *   Z = A^_m H W (+ bias),  Hout = act(Z).
+ *   H        device [nc x d_in] (ldh): owned rows, then halo rows.
+ *   W        device f32 [d_in x d_out], dense (ld = d_out).   bias: device f32[d_out] or NULL.
+ *   Z        device [nr x d_out] (ld = d_out) or NULL: pre-activation values.
+ *   Hout     device [nr x d_out] (ld = d_out), required.
+ *   AH_save  device [nr x d_in] (ld = d_in) or NULL.  When given, the layer is evaluated as
+ *            (A^ H) W and A^ H is stored here for the backward pass; otherwise the library
+ *            picks the cheaper of (A^ H) W and A^ (H W).  Both are the same sum; only the
+ *            rounding order differs.
+ */
+int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W,
+                  const float* bias, int d_in, int d_out, int act, int dtype, void* Z, void* Hout,
+                  void* AH_save, void* stream);
+
+/*
+ * Backward pass of one layer on the block (Sec. 3.1 second and third equations, Sec. 4.2):
+ *   dW    = (A^_m H)^T G                 f32 [d_in x d_out]  (this block's partial sum)
+ *   dbias = column sums of G             f32 [d_out] or NULL
+ *   dH    = (A^_m^T G W^T) (.) [Zprev>0] [nc x d_in] (ld = d_in) or NULL (first layer: skipped).
+ *           The mask covers the owned rows (Zprev is [nr x d_in], ld = d_in; NULL = no mask);
+ *           halo rows nr..nc-1 are this block's unmasked contributions to rows owned elsewhere.
+ *   H        device [nc x d_in] (ldh), the layer's input.
+ *   AH_saved device [nr x d_in] from gcn_layer_fwd or NULL.
+ *   G        device [nr x d_out] (ld = d_out): gradient w.r.t. this layer's Z.
+ * Needs GCN_BUILD_CSC when dH is requested.
+ */
+int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, const void* AH_saved,
+                  const float* W, int d_in, int d_out, int dtype, const void* G,
+                  const void* Zprev, float* dW, float* dbias, void* dH, void* stream);
+
+/*
+ * Output-layer loss and gradient (Sec. 3.1: G^L = grad J (.) act'(Z^L), identity activation on
+ * the last layer, J = softmax cross-entropy):
+ *   loss = -scale * sum_i log softmax(Z_i)[y_i],   G = scale * (softmax(Z) - onehot(y)).
+ *   Z     device [nr x C] (ldz), element type dtype.   y: device int32[nr]; y[i] < 0 means
+ *         "no label": no loss term, zero gradient row; y[i] >= C is treated the same way.
+ *   loss  device f32 scalar (accumulated in fp64 in a fixed order: run-to-run identical).
+ *   G     device [nr x C] (ldg), element type dtype.
+ * The per-block partial sums live in a fixed device buffer of the library: two calls that
+ * overlap in time on the same GPU race on it.
+ */
+int gcn_softmax_xent(const void* Z, int64_t ldz, int64_t nr, int C, int dtype, const int32_t* y,
+                     float scale, float* loss, void* G, int64_t ldg, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GCN_H_ */

@@ -1,0 +1,12 @@
+"""MI355X-native GCN layer path: Python binding over the C-ABI library ``libgcn.so``.
+
+The binding only marshals arguments (torch tensors -> device pointers, current stream);
+every step of the path runs in the library's HIP kernels.  Importing this package fails
+loudly if the library has not been built (``python -m paper_2212_05009_amd.build`` or
+``__graft_entry__.build()``); there is no CPU fallback.
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, EPI_NONE, EPI_RELU, EPI_MASK, ACT_NONE, ACT_RELU, BUILD_CSC,
+    Csr, GcnError, gcn_csr_build, gcn_spmm, gcn_spmm_t, gcn_halo_gather, gcn_layer_fwd,
+    gcn_layer_bwd, gcn_softmax_xent, library_path,
+)

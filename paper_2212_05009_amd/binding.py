@@ -1,0 +1,265 @@
+"""ctypes binding of include/gcn.h: same names, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgcn.so")
+
+F32, BF16 = 0, 1
+BUILD_CSC = 1
+EPI_NONE, EPI_RELU, EPI_MASK = 0, 1, 2
+ACT_NONE, ACT_RELU = 0, 1
+
+
+class GcnError(RuntimeError):
+    pass
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build the HIP library first "
+            "(python -m paper_2212_05009_amd.build); there is no fallback path")
+    lib = C.CDLL(_LIB_PATH)
+    i32p, i64p, f32p, vp = C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_float), C.c_void_p
+    lib.gcn_last_error.restype = C.c_char_p
+    lib.gcn_last_error.argtypes = []
+    lib.gcn_csr_build.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int64, C.c_int64, vp, C.c_int, vp, C.POINTER(vp)]
+    lib.gcn_csr_info.argtypes = [vp, i64p, i64p, i64p]
+    lib.gcn_csr_arrays.argtypes = [vp] + [C.POINTER(vp)] * 8
+    lib.gcn_csr_free.argtypes = [vp]
+    lib.gcn_spmm.argtypes = [vp, vp, C.c_int64, C.c_int, C.c_int, vp, C.c_int64, C.c_int, vp, vp, C.c_int64, vp]
+    lib.gcn_spmm_t.argtypes = [vp, vp, C.c_int64, C.c_int, C.c_int, vp, C.c_int64, C.c_int, vp, C.c_int64, vp]
+    lib.gcn_halo_gather.argtypes = [vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, C.c_int64, vp, C.c_int64, vp]
+    lib.gcn_layer_fwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]
+    lib.gcn_layer_bwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp]
+    lib.gcn_softmax_xent.argtypes = [vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, C.c_float, vp, vp, C.c_int64, vp]
+    for name in ("gcn_csr_build", "gcn_csr_info", "gcn_csr_arrays", "gcn_csr_free", "gcn_spmm", "gcn_spmm_t",
+                 "gcn_halo_gather", "gcn_layer_fwd", "gcn_layer_bwd", "gcn_softmax_xent"):
+        getattr(lib, name).restype = C.c_int
+    return lib
+
+
+_lib = _load()
+_hip = C.CDLL("libamdhip64.so.7")     # already loaded by torch; same runtime instance as the library's
+_hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+_hip.hipMemcpy.restype = C.c_int
+
+
+def _hip_memcpy(dst: int, src: int, nbytes: int) -> int:
+    return _hip.hipMemcpy(C.c_void_p(dst), C.c_void_p(src), C.c_size_t(nbytes), 3)   # 3 = device to device
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise GcnError(f"{what} failed ({rc}): {_lib.gcn_last_error().decode()}")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported feature dtype {t.dtype}")
+
+
+def _dev(t: torch.Tensor, dtype=None, what="tensor"):
+    if not t.is_cuda:
+        raise TypeError(f"{what} must live on the GPU")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{what} must have dtype {dtype}, got {t.dtype}")
+    return t
+
+
+def _rowmajor(t: torch.Tensor, what="matrix"):
+    """(ld, d): accepts 2-D tensors whose rows are contiguous (row stride >= number of columns)."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1) or t.stride(0) < t.shape[1]:
+        raise TypeError(f"{what} must be a row-major 2-D tensor")
+    return t.stride(0), t.shape[1]
+
+
+class Csr:
+    """Owning wrapper of a gcn_csr_t handle."""
+
+    def __init__(self, handle, device):
+        self._h = handle
+        self.device = device
+        nr, nh, nnz = C.c_int64(), C.c_int64(), C.c_int64()
+        _check(_lib.gcn_csr_info(self._h, C.byref(nr), C.byref(nh), C.byref(nnz)), "gcn_csr_info")
+        self.nr, self.nh, self.nnz = nr.value, nh.value, nnz.value
+        self.nc = self.nr + self.nh
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise GcnError("handle already freed")
+        return self._h
+
+    def arrays(self):
+        """Copies of the device arrays as torch tensors (for inspection and parity checks)."""
+        ptrs = [C.c_void_p() for _ in range(8)]
+        _check(_lib.gcn_csr_arrays(self.handle, *[C.byref(p) for p in ptrs]), "gcn_csr_arrays")
+        spec = [("rowptr", torch.int64, self.nr + 1), ("col", torch.int32, self.nnz), ("val", torch.float32, self.nnz),
+                ("deg", torch.int32, self.nr), ("halo_gid", torch.int32, self.nh),
+                ("colptr", torch.int64, self.nc + 1), ("rowidx", torch.int32, self.nnz), ("val_t", torch.float32, self.nnz)]
+        out = {}
+        torch.cuda.synchronize()
+        for p, (name, dt, n) in zip(ptrs, spec):
+            if not p.value:
+                out[name] = None
+                continue
+            t = torch.empty(n, dtype=dt, device=self.device)
+            if n:
+                rc = _hip_memcpy(t.data_ptr(), p.value, n * t.element_size())
+                if int(rc) != 0:
+                    raise GcnError(f"copy of {name} failed: {rc}")
+            out[name] = t
+        return out
+
+    def free(self):
+        if self._h is not None:
+            _lib.gcn_csr_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def gcn_csr_build(src: torch.Tensor, dst: torch.Tensor, n_global: int, row_lo: int = 0, row_hi: int | None = None,
+                  deg_global: torch.Tensor | None = None, flags: int = BUILD_CSC) -> Csr:
+    _dev(src, torch.int32, "src"); _dev(dst, torch.int32, "dst")
+    if src.numel() != dst.numel() or not src.is_contiguous() or not dst.is_contiguous():
+        raise TypeError("src/dst must be contiguous int32 vectors of equal length")
+    if deg_global is not None:
+        _dev(deg_global, torch.int32, "deg_global")
+        if deg_global.numel() != n_global or not deg_global.is_contiguous():
+            raise TypeError("deg_global must be a contiguous int32 vector of length n_global")
+    row_hi = n_global if row_hi is None else row_hi
+    out = C.c_void_p()
+    with torch.cuda.device(src.device):
+        rc = _lib.gcn_csr_build(_ptr(src), _ptr(dst), src.numel(), n_global, row_lo, row_hi, _ptr(deg_global), flags,
+                                _stream(), C.byref(out))
+    _check(rc, "gcn_csr_build")
+    return Csr(out, src.device)
+
+
+def gcn_spmm(A: Csr, X: torch.Tensor, Y: torch.Tensor, epilogue: int = EPI_NONE, bias: torch.Tensor | None = None,
+             Zprev: torch.Tensor | None = None):
+    ldx, d = _rowmajor(_dev(X), "X"); ldy, dy = _rowmajor(_dev(Y), "Y")
+    if X.shape[0] != A.nc or Y.shape[0] != A.nr or dy != d or Y.dtype != X.dtype:
+        raise TypeError("gcn_spmm: X must be [nc, d] and Y [nr, d] of the same dtype")
+    ldz = 0
+    if Zprev is not None:
+        ldz, dz = _rowmajor(_dev(Zprev, X.dtype, "Zprev"), "Zprev")
+        if Zprev.shape[0] != A.nr or dz != d:
+            raise TypeError("gcn_spmm: Zprev must be [nr, d]")
+    if bias is not None and (_dev(bias, torch.float32, "bias").numel() != d or not bias.is_contiguous()):
+        raise TypeError("gcn_spmm: bias must be a contiguous f32 vector of length d")
+    _check(_lib.gcn_spmm(A.handle, _ptr(X), ldx, d, _dtype_code(X), _ptr(Y), ldy, epilogue, _ptr(bias), _ptr(Zprev),
+                         ldz, _stream()), "gcn_spmm")
+    return Y
+
+
+def gcn_spmm_t(A: Csr, X: torch.Tensor, Y: torch.Tensor, epilogue: int = EPI_NONE, Zprev: torch.Tensor | None = None):
+    ldx, d = _rowmajor(_dev(X), "X"); ldy, dy = _rowmajor(_dev(Y), "Y")
+    if X.shape[0] != A.nr or Y.shape[0] != A.nc or dy != d or Y.dtype != X.dtype:
+        raise TypeError("gcn_spmm_t: X must be [nr, d] and Y [nc, d] of the same dtype")
+    ldz = 0
+    if Zprev is not None:
+        ldz, dz = _rowmajor(_dev(Zprev, X.dtype, "Zprev"), "Zprev")
+        if Zprev.shape[0] != A.nr or dz != d:
+            raise TypeError("gcn_spmm_t: Zprev must be [nr, d]")
+    _check(_lib.gcn_spmm_t(A.handle, _ptr(X), ldx, d, _dtype_code(X), _ptr(Y), ldy, epilogue, _ptr(Zprev), ldz,
+                           _stream()), "gcn_spmm_t")
+    return Y
+
+
+def gcn_halo_gather(table: torch.Tensor, idx: torch.Tensor, recv: torch.Tensor):
+    """table may be a GPU tensor or a pinned host tensor."""
+    if not (table.is_cuda or table.is_pinned()):
+        raise TypeError("table must be a GPU tensor or pinned host memory")
+    ld, d = _rowmajor(table, "table"); ldr, dr = _rowmajor(_dev(recv), "recv")
+    _dev(idx, torch.int32, "idx")
+    if dr != d or recv.shape[0] != idx.numel() or recv.dtype != table.dtype or not idx.is_contiguous():
+        raise TypeError("gcn_halo_gather: recv must be [len(idx), d] of the table's dtype")
+    _check(_lib.gcn_halo_gather(_ptr(table), ld, table.shape[0], d, _dtype_code(table), _ptr(idx), idx.numel(),
+                                _ptr(recv), ldr, _stream()), "gcn_halo_gather")
+    return recv
+
+
+def _dense(t, rows, cols, dtype, what):
+    _dev(t, dtype, what)
+    if t.shape != (rows, cols) or not t.is_contiguous():
+        raise TypeError(f"{what} must be a contiguous [{rows}, {cols}] tensor")
+    return t
+
+
+def gcn_layer_fwd(A: Csr, H: torch.Tensor, W: torch.Tensor, Hout: torch.Tensor, act: int = ACT_RELU,
+                  bias: torch.Tensor | None = None, Z: torch.Tensor | None = None, AH_save: torch.Tensor | None = None):
+    ldh, d_in = _rowmajor(_dev(H), "H")
+    if H.shape[0] != A.nc:
+        raise TypeError("gcn_layer_fwd: H must have nc rows")
+    d_out = W.shape[1]
+    _dense(W, d_in, d_out, torch.float32, "W")
+    _dense(Hout, A.nr, d_out, H.dtype, "Hout")
+    if Z is not None:
+        _dense(Z, A.nr, d_out, H.dtype, "Z")
+    if AH_save is not None:
+        _dense(AH_save, A.nr, d_in, H.dtype, "AH_save")
+    if bias is not None:
+        _dense(bias.view(1, -1), 1, d_out, torch.float32, "bias")
+    _check(_lib.gcn_layer_fwd(A.handle, _ptr(H), ldh, _ptr(W), _ptr(bias), d_in, d_out, act, _dtype_code(H), _ptr(Z),
+                              _ptr(Hout), _ptr(AH_save), _stream()), "gcn_layer_fwd")
+    return Hout
+
+
+def gcn_layer_bwd(A: Csr, H: torch.Tensor, W: torch.Tensor, G: torch.Tensor, dW: torch.Tensor,
+                  dH: torch.Tensor | None = None, Zprev: torch.Tensor | None = None,
+                  AH_saved: torch.Tensor | None = None, dbias: torch.Tensor | None = None):
+    ldh, d_in = _rowmajor(_dev(H), "H")
+    if H.shape[0] != A.nc:
+        raise TypeError("gcn_layer_bwd: H must have nc rows")
+    d_out = W.shape[1]
+    _dense(W, d_in, d_out, torch.float32, "W")
+    _dense(G, A.nr, d_out, H.dtype, "G")
+    _dense(dW, d_in, d_out, torch.float32, "dW")
+    if dH is not None:
+        _dense(dH, A.nc, d_in, H.dtype, "dH")
+    if Zprev is not None:
+        _dense(Zprev, A.nr, d_in, H.dtype, "Zprev")
+    if AH_saved is not None:
+        _dense(AH_saved, A.nr, d_in, H.dtype, "AH_saved")
+    if dbias is not None:
+        _dense(dbias.view(1, -1), 1, d_out, torch.float32, "dbias")
+    _check(_lib.gcn_layer_bwd(A.handle, _ptr(H), ldh, _ptr(AH_saved), _ptr(W), d_in, d_out, _dtype_code(H), _ptr(G),
+                              _ptr(Zprev), _ptr(dW), _ptr(dbias), _ptr(dH), _stream()), "gcn_layer_bwd")
+    return dW
+
+
+def gcn_softmax_xent(Z: torch.Tensor, y: torch.Tensor, scale: float, loss: torch.Tensor, G: torch.Tensor):
+    ldz, Cn = _rowmajor(_dev(Z), "Z"); ldg, cg = _rowmajor(_dev(G, Z.dtype, "G"), "G")
+    _dev(y, torch.int32, "y"); _dev(loss, torch.float32, "loss")
+    if cg != Cn or G.shape[0] != Z.shape[0] or y.numel() != Z.shape[0] or not y.is_contiguous() or loss.numel() != 1:
+        raise TypeError("gcn_softmax_xent: shape mismatch")
+    _check(_lib.gcn_softmax_xent(_ptr(Z), ldz, Z.shape[0], Cn, _dtype_code(Z), _ptr(y), float(scale), _ptr(loss),
+                                 _ptr(G), ldg, _stream()), "gcn_softmax_xent")
+    return loss

@@ -1,0 +1,134 @@
+// Shared host-side declarations of the gfx950 GCN library (internal; the public ABI is gcn.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/gcn.h"
+
+namespace gcn {
+
+// ---- error reporting -------------------------------------------------------------------
+int fail(int code, const char* fmt, ...);   // records the thread-local message, returns code
+void clear_error();
+
+#define GCN_HIP(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t e__ = (expr);                                                               \
+    if (e__ != hipSuccess)                                                                 \
+      return ::gcn::fail(e__ == hipErrorOutOfMemory ? GCN_ENOMEM : GCN_EHIP, "%s: %s",     \
+                         #expr, hipGetErrorString(e__));                                   \
+  } while (0)
+
+#define GCN_TRY(expr)            \
+  do {                           \
+    int rc__ = (expr);           \
+    if (rc__ != GCN_OK) return rc__; \
+  } while (0)
+
+#define GCN_CHECK_LAUNCH() GCN_HIP(hipGetLastError())
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+// ---- execution schedule of a compressed sparse matrix (row binning) ----------------------
+// Rows are split by length.  Rows longer than kHubRowNnz ("hub" rows of a power-law graph)
+// are cut into chunks of kHubChunkNnz entries, one 256-thread block per chunk; their partial
+// sums are combined by a finalisation kernel.  All other rows get one wavefront each, in an
+// order that starts the longest rows first.  The schedule only fixes the order of execution
+// and the chunking; the matrix arrays stay in row order.
+constexpr int kHubRowNnz = 2048;
+constexpr int kHubChunkNnz = 1024;
+
+struct Schedule {
+  int32_t* wave_rows = nullptr;   // [n_wave_rows] rows handled one wavefront each
+  int64_t n_wave_rows = 0;
+  int32_t* hub_rows = nullptr;    // [n_hub_rows] rows handled by chunks
+  int64_t n_hub_rows = 0;
+  int64_t* hub_chunk_ptr = nullptr;  // [n_hub_rows+1] first chunk of each hub row
+  int32_t* chunk_hub = nullptr;      // [n_chunks] index into hub_rows of each chunk
+  int64_t n_chunks = 0;
+};
+
+}  // namespace gcn
+
+// ---- the opaque handle -------------------------------------------------------------------
+struct gcn_csr {
+  int device = 0;
+  int64_t n_global = 0, row_lo = 0;
+  int64_t nr = 0, nh = 0, nc = 0, nnz = 0;
+  int64_t* rowptr = nullptr;
+  int32_t* col = nullptr;
+  float* val = nullptr;
+  int32_t* deg = nullptr;
+  int32_t* halo_gid = nullptr;
+  int64_t* colptr = nullptr;
+  int32_t* rowidx = nullptr;
+  float* val_t = nullptr;
+  gcn::Schedule sched;     // for A   (rows = owned rows)
+  gcn::Schedule sched_t;   // for A^T (rows = local columns)
+  void* ws = nullptr;      // scratch workspace, grown on demand
+  size_t ws_bytes = 0;
+};
+
+namespace gcn {
+
+// Makes sure the handle's workspace holds at least `bytes`; may synchronise the device when it
+// has to grow (the old buffer could still be in use by enqueued work).
+int ensure_workspace(gcn_csr* A, size_t bytes);
+
+// ---- device primitives (scan_sort.hip) ----------------------------------------------------
+// out[i] = sum_{k<i} in[k] for i in [0, n]; out has n+1 entries (out[n] = total).
+// tmp must hold scan_tmp_bytes(n).
+size_t scan_tmp_bytes(int64_t n);
+int exclusive_scan_u32(const uint32_t* in, int64_t* out, int64_t n, void* tmp, hipStream_t s);
+
+// Stable least-significant-digit radix sort of 64-bit keys on bits [bit_lo, bit_hi), with an
+// optional 32-bit payload.  Result ends in (keys_out, pay_out); both key buffers and both
+// payload buffers are clobbered.  tmp must hold sort_tmp_bytes(n).
+size_t sort_tmp_bytes(int64_t n);
+int radix_sort_u64(uint64_t* keys_a, uint64_t* keys_b, uint32_t* pay_a, uint32_t* pay_b, int64_t n,
+                   int bit_lo, int bit_hi, void* tmp, hipStream_t s, uint64_t** keys_out,
+                   uint32_t** pay_out);
+
+// ---- schedule construction (csr_build.hip) -------------------------------------------------
+int build_schedule(const int64_t* ptr, int64_t n_rows, hipStream_t s, Schedule* out);
+void free_schedule(Schedule* sc);
+
+// ---- kernels behind the public entry points -------------------------------------------------
+struct SpmmArgs {
+  const int64_t* ptr; const int32_t* idx; const float* val; const Schedule* sched;
+  int64_t n_rows;            // rows of the sparse matrix (= rows of Y)
+  int64_t n_mask_rows;       // rows covered by bias / relu / mask epilogues that need Zprev
+  const void* X; int64_t ldx;
+  void* Y; int64_t ldy;      // epilogue result
+  void* Y2; int64_t ldy2;    // optional second output: the value before ReLU (may be null)
+  int d; int dtype; int epilogue; const float* bias; const void* Zprev; int64_t ldz;
+};
+// ws: workspace for hub partial sums, at least spmm_ws_bytes(sched, d)
+size_t spmm_ws_bytes(const Schedule* sc, int d);
+int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s);
+
+struct GemmEpilogue {
+  const float* bias = nullptr;   // [N] added to every row
+  int relu = 0;                  // C = max(.,0)
+  const void* mask = nullptr;    // [mask_rows x N] (ld = ldmask): C *= [mask > 0] for rows < mask_rows
+  int64_t ldmask = 0, mask_rows = 0;
+  void* C2 = nullptr;            // optional second output: value before ReLU
+  int64_t ldc2 = 0;
+};
+// C[M x N] = A[M x K] * B[K x N];  A, C (and C2, mask) have element type dtype, B is f32.
+int gemm_nn(const void* A, int64_t lda, const float* B, int64_t ldb, void* C, int64_t ldc,
+            int64_t M, int N, int K, int dtype, const GemmEpilogue& epi, hipStream_t s);
+// C[M x N] (f32) = A[Kdim x M]^T * B[Kdim x N], Kdim huge: split over blocks, partial tiles in ws
+// (gemm_tn_ws_bytes), then summed in a fixed order.  A, B element type dtype.
+size_t gemm_tn_ws_bytes(int64_t Kdim, int M, int N);
+int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc,
+            int64_t Kdim, int M, int N, int dtype, void* ws, hipStream_t s);
+// Wt[N x K] = W[K x N]^T (f32, small)
+int transpose_f32(const float* W, int K, int N, float* Wt, hipStream_t s);
+// out[c] = sum_i G[i, c]  (deterministic), ws at least colsum_ws_bytes
+size_t colsum_ws_bytes(int64_t rows, int N);
+int colsum(const void* G, int64_t ldg, int64_t rows, int N, int dtype, float* out, void* ws,
+           hipStream_t s);
+
+}  // namespace gcn

@@ -1,0 +1,142 @@
+// gcn_layer_fwd / gcn_layer_bwd: one GCN layer on a row block, composed from the sparse and
+// dense kernels (Sec. 3.1 equations for Z, S and dW; Sec. 4.1 / 4.2 for the block form).
+//
+// The three-matrix products are associative, so the order is chosen by cost; every choice is
+// the same real-number sum:
+//   forward   (A H) W   sparse product at width d_in  (also what Sec. 4.1 writes), or
+//             A (H W)   sparse product at width d_out, dense product over all nc rows;
+//   backward  T = A^T G at width d_out, then dH = T W^T and dW = H^T T  (Sec. 4.2 notes that the
+//             sparse product with G is shared between S and dW), or
+//             Q = G W^T, dH = A^T Q at width d_in, and dW = (A H)^T G.
+#include "common.h"
+
+namespace gcn {
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+static size_t es_of(int dtype) { return dtype == GCN_BF16 ? 2 : 4; }
+
+struct Carver {              // hands out 256-byte aligned pieces of the workspace
+  char* base; size_t used = 0;
+  void* take(size_t bytes) { void* p = base ? base + used : nullptr; used += align256(bytes); return p; }
+};
+
+}  // namespace gcn
+
+using namespace gcn;
+
+extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W, const float* bias,
+                             int d_in, int d_out, int act, int dtype, void* Z, void* Hout, void* AH_save,
+                             void* stream) {
+  clear_error();
+  if (!A || !H || !W || !Hout) return fail(GCN_EINVAL, "gcn_layer_fwd: NULL argument");
+  if (d_in < 1 || d_out < 1 || ldh < d_in) return fail(GCN_EINVAL, "gcn_layer_fwd: bad dimensions");
+  if (act != GCN_ACT_NONE && act != GCN_ACT_RELU) return fail(GCN_EINVAL, "gcn_layer_fwd: unknown activation");
+  if (dtype != GCN_F32 && dtype != GCN_BF16) return fail(GCN_EINVAL, "gcn_layer_fwd: unknown dtype");
+  gcn_csr* Am = const_cast<gcn_csr*>(A);
+  hipStream_t s = (hipStream_t)stream;
+  const size_t es = es_of(dtype);
+  // sparse-first costs nnz*d_in gathers and a dense product over nr rows; dense-first costs
+  // nnz*d_out gathers and a dense product over nc rows
+  const bool sparse_first = AH_save != nullptr || d_in <= d_out;
+  const int relu = act == GCN_ACT_RELU;
+
+  for (int pass = 0; pass < 2; ++pass) {      // pass 0 sizes the workspace, pass 1 runs
+    Carver ws{pass ? (char*)Am->ws : nullptr};
+    void* hub = ws.take(spmm_ws_bytes(&A->sched, sparse_first ? d_in : d_out));
+    if (sparse_first) {
+      void* AH = AH_save ? AH_save : ws.take((size_t)A->nr * d_in * es);
+      if (pass) {
+        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nr, H, ldh, AH, d_in, nullptr, 0,
+                    d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+        GCN_TRY(spmm_launch(sp, hub, s));
+        GemmEpilogue epi;
+        epi.bias = bias; epi.relu = relu; epi.C2 = Z; epi.ldc2 = d_out;
+        GCN_TRY(gemm_nn(AH, d_in, W, d_out, Hout, d_out, A->nr, d_out, d_in, dtype, epi, s));
+      }
+    } else {
+      const int64_t ldp = round_up(d_out, 4);
+      void* P = ws.take((size_t)A->nc * ldp * es);
+      if (pass) {
+        GemmEpilogue epi;
+        GCN_TRY(gemm_nn(H, ldh, W, d_out, P, ldp, A->nc, d_out, d_in, dtype, epi, s));
+        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nr, P, ldp, Hout, d_out, Z, d_out,
+                    d_out, dtype, relu ? GCN_EPI_RELU : GCN_EPI_NONE, bias, nullptr, 0};
+        GCN_TRY(spmm_launch(sp, hub, s));
+      }
+    }
+    if (!pass) GCN_TRY(ensure_workspace(Am, ws.used));
+  }
+  return GCN_OK;
+}
+
+extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, const void* AH_saved, const float* W,
+                             int d_in, int d_out, int dtype, const void* G, const void* Zprev, float* dW,
+                             float* dbias, void* dH, void* stream) {
+  clear_error();
+  if (!A || !H || !W || !G || !dW) return fail(GCN_EINVAL, "gcn_layer_bwd: NULL argument");
+  if (d_in < 1 || d_out < 1 || ldh < d_in) return fail(GCN_EINVAL, "gcn_layer_bwd: bad dimensions");
+  if (dtype != GCN_F32 && dtype != GCN_BF16) return fail(GCN_EINVAL, "gcn_layer_bwd: unknown dtype");
+  if (dH && !A->colptr) return fail(GCN_EINVAL, "gcn_layer_bwd: dH needs a handle built with GCN_BUILD_CSC");
+  gcn_csr* Am = const_cast<gcn_csr*>(A);
+  hipStream_t s = (hipStream_t)stream;
+  const size_t es = es_of(dtype);
+  const bool have_csc = A->colptr != nullptr;
+  // share one transposed sparse product of width d_out between dH and dW when that is narrower
+  const bool via_T = have_csc && d_out < d_in && (dH != nullptr || AH_saved == nullptr);
+
+  for (int pass = 0; pass < 2; ++pass) {
+    Carver ws{pass ? (char*)Am->ws : nullptr};
+    const int dmax = d_in > d_out ? d_in : d_out;
+    size_t hub_bytes = spmm_ws_bytes(&A->sched, dmax);
+    if (have_csc && spmm_ws_bytes(&A->sched_t, dmax) > hub_bytes) hub_bytes = spmm_ws_bytes(&A->sched_t, dmax);
+    void* hub = ws.take(hub_bytes);
+    float* Wt = (float*)ws.take(sizeof(float) * (size_t)d_in * d_out);
+    void* cs = dbias ? ws.take(colsum_ws_bytes(A->nr, d_out)) : nullptr;
+    if (pass && dbias) GCN_TRY(colsum(G, d_out, A->nr, d_out, dtype, dbias, cs, s));
+
+    if (via_T) {
+      const int64_t ldt = round_up(d_out, 4);
+      void* T = ws.take((size_t)A->nc * ldt * es);
+      const int64_t kd = AH_saved ? A->nr : A->nc;
+      void* tn = ws.take(gemm_tn_ws_bytes(kd, d_in, d_out));
+      if (pass) {
+        SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, G, d_out, T, ldt, nullptr, 0,
+                    d_out, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+        GCN_TRY(spmm_launch(sp, hub, s));
+        if (dH) {
+          GCN_TRY(transpose_f32(W, d_in, d_out, Wt, s));
+          GemmEpilogue epi;
+          epi.mask = Zprev; epi.ldmask = d_in; epi.mask_rows = Zprev ? A->nr : 0;
+          GCN_TRY(gemm_nn(T, ldt, Wt, d_in, dH, d_in, A->nc, d_in, d_out, dtype, epi, s));
+        }
+        if (AH_saved) GCN_TRY(gemm_tn(AH_saved, d_in, G, d_out, dW, d_out, A->nr, d_in, d_out, dtype, tn, s));
+        else GCN_TRY(gemm_tn(H, ldh, T, ldt, dW, d_out, A->nc, d_in, d_out, dtype, tn, s));
+      }
+    } else {
+      const int64_t ldq = round_up(d_in, 4);
+      void* Q = dH ? ws.take((size_t)A->nr * ldq * es) : nullptr;
+      void* AH = AH_saved ? nullptr : ws.take((size_t)A->nr * ldq * es);
+      void* tn = ws.take(gemm_tn_ws_bytes(A->nr, d_in, d_out));
+      if (pass) {
+        if (dH) {
+          GCN_TRY(transpose_f32(W, d_in, d_out, Wt, s));
+          GemmEpilogue epi;
+          GCN_TRY(gemm_nn(G, d_out, Wt, d_in, Q, ldq, A->nr, d_in, d_out, dtype, epi, s));
+          SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, Q, ldq, dH, d_in, nullptr, 0,
+                      d_in, dtype, Zprev ? GCN_EPI_MASK : GCN_EPI_NONE, nullptr, Zprev, d_in};
+          GCN_TRY(spmm_launch(sp, hub, s));
+        }
+        const void* ah = AH_saved; int64_t ldah = d_in;
+        if (!AH_saved) {
+          SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nr, H, ldh, AH, ldq, nullptr, 0,
+                      d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+          GCN_TRY(spmm_launch(sp, hub, s));
+          ah = AH; ldah = ldq;
+        }
+        GCN_TRY(gemm_tn(ah, ldah, G, d_out, dW, d_out, A->nr, d_in, d_out, dtype, tn, s));
+      }
+    }
+    if (!pass) GCN_TRY(ensure_workspace(Am, ws.used));
+  }
+  return GCN_OK;
+}

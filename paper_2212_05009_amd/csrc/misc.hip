@@ -1,0 +1,198 @@
+// Error bookkeeping, the halo gather and the softmax cross-entropy of the gfx950 GCN library.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "common.h"
+
+namespace gcn {
+
+static thread_local char g_err[512] = {0};
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+void clear_error() { g_err[0] = 0; }
+
+typedef uint16_t bf16_t;
+
+// ------------------------------------------------------------------------------------------
+// Halo gather (Sec. 4.1: the rows of H selected by an index set are copied into the buffer of
+// received rows).  A row is moved as n_vec units of VB bytes; a group of LPR lanes owns a row,
+// so that one request covers a whole feature row whenever it fits.
+// ------------------------------------------------------------------------------------------
+template <int VB> struct Unit;
+template <> struct Unit<16> { typedef uint4 type; };
+template <> struct Unit<8> { typedef uint2 type; };
+template <> struct Unit<4> { typedef uint32_t type; };
+template <> struct Unit<2> { typedef uint16_t type; };
+
+template <int VB, int LPR>
+__global__ __launch_bounds__(256) void k_gather(const char* __restrict__ table, int64_t ld_bytes,
+                                                int64_t n_table_rows, int n_vec,
+                                                const int32_t* __restrict__ idx, int64_t n_idx,
+                                                char* __restrict__ recv, int64_t ldr_bytes) {
+  typedef typename Unit<VB>::type U;
+  constexpr int G = 256 / LPR;
+  const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
+  const int64_t s = (int64_t)blockIdx.x * G + g;
+  if (s >= n_idx) return;
+  const int64_t j = idx[s];
+  const bool ok = j >= 0 && j < n_table_rows;
+  const U* __restrict__ src = reinterpret_cast<const U*>(table + (ok ? j : 0) * ld_bytes);
+  U* __restrict__ dst = reinterpret_cast<U*>(recv + s * ldr_bytes);
+  for (int u = l; u < n_vec; u += LPR) {
+    U v;
+    if (ok) v = src[u];
+    else memset(&v, 0, sizeof(U));
+    dst[u] = v;
+  }
+}
+
+template <int VB>
+static int gather_v(const char* table, int64_t ldb, int64_t nt, int n_vec, const int32_t* idx, int64_t n_idx,
+                    char* recv, int64_t ldrb, hipStream_t s) {
+  auto grid = [&](int lpr) { return dim3((unsigned)ceil_div(n_idx, 256 / lpr)); };
+  if (n_vec <= 4) k_gather<VB, 4><<<grid(4), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
+  else if (n_vec <= 8) k_gather<VB, 8><<<grid(8), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
+  else if (n_vec <= 16) k_gather<VB, 16><<<grid(16), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
+  else if (n_vec <= 32) k_gather<VB, 32><<<grid(32), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
+  else k_gather<VB, 64><<<grid(64), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
+  GCN_CHECK_LAUNCH();
+  return GCN_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Softmax cross-entropy (Sec. 3.1, the output-layer gradient, with identity activation on the
+// last layer): one group of LPR lanes per row.  The loss terms are added in fp64: per thread,
+// then per block in a fixed tree, then over the blocks in block order.
+// ------------------------------------------------------------------------------------------
+constexpr int kLossBlocks = 1024;
+__device__ double g_loss_partial[kLossBlocks];
+
+template <typename T> __device__ __forceinline__ float ldf(const T* p) {
+  if constexpr (sizeof(T) == 4) return (float)*p; else return __uint_as_float((uint32_t)(*p) << 16);
+}
+template <typename T> __device__ __forceinline__ void stf(T* p, float f) {
+  if constexpr (sizeof(T) == 4) { *p = f; }
+  else {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) { *p = (T)((u >> 16) | 0x40u); return; }
+    u += 0x7fffu + ((u >> 16) & 1u);
+    *p = (T)(u >> 16);
+  }
+}
+
+template <typename T, int LPR>
+__global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, int64_t ldz, int64_t nr, int C,
+                                                      const int32_t* __restrict__ y, float scale,
+                                                      T* __restrict__ G, int64_t ldg) {
+  constexpr int GR = 256 / LPR;
+  const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
+  double local = 0.0;
+  for (int64_t row = (int64_t)blockIdx.x * GR + g; row < nr; row += (int64_t)gridDim.x * GR) {
+    const T* z = Z + row * ldz;
+    T* go = G + row * ldg;
+    const int label = y[row];
+    if (label < 0 || label >= C) {                 // no label: no loss term, zero gradient
+      for (int c = l; c < C; c += LPR) stf<T>(go + c, 0.f);
+      continue;
+    }
+    float mx = -INFINITY;
+    for (int c = l; c < C; c += LPR) mx = fmaxf(mx, ldf<T>(z + c));
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    float se = 0.f;
+    for (int c = l; c < C; c += LPR) se += expf(ldf<T>(z + c) - mx);
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) se += __shfl_xor(se, off, 64);
+    const float inv = 1.0f / se;
+    for (int c = l; c < C; c += LPR) {
+      float p = expf(ldf<T>(z + c) - mx) * inv;
+      stf<T>(go + c, scale * (p - (c == label ? 1.f : 0.f)));
+    }
+    if (l == 0) local += (double)(mx + logf(se)) - (double)ldf<T>(z + label);
+  }
+  // block sum in a fixed tree
+  __shared__ double red[256];
+  red[threadIdx.x] = local;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) g_loss_partial[blockIdx.x] = red[0];
+}
+
+__global__ void k_loss_finish(int nblocks, float scale, float* __restrict__ loss) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    double s = 0.0;
+    for (int b = 0; b < nblocks; ++b) s += g_loss_partial[b];
+    *loss = (float)((double)scale * s);
+  }
+}
+
+template <typename T>
+static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* y, float scale, float* loss, T* G,
+                     int64_t ldg, hipStream_t s) {
+  int lpr = 4;
+  while (lpr < 64 && lpr < C) lpr <<= 1;
+  int64_t want = ceil_div(nr > 0 ? nr : 1, 256 / lpr);
+  int nb = (int)(want < kLossBlocks ? want : kLossBlocks);
+  switch (lpr) {
+    case 4: k_softmax_xent<T, 4><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+    case 8: k_softmax_xent<T, 8><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+    case 16: k_softmax_xent<T, 16><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+    case 32: k_softmax_xent<T, 32><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+    default: k_softmax_xent<T, 64><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+  }
+  k_loss_finish<<<1, 64, 0, s>>>(nb, scale, loss);
+  GCN_CHECK_LAUNCH();
+  return GCN_OK;
+}
+
+}  // namespace gcn
+
+using namespace gcn;
+
+extern "C" const char* gcn_last_error(void) { return g_err; }
+
+extern "C" int gcn_halo_gather(const void* table, int64_t ld, int64_t n_table_rows, int d, int dtype,
+                               const int32_t* d_idx, int64_t n_idx, void* recv, int64_t ldr, void* stream) {
+  clear_error();
+  if (n_idx < 0 || n_table_rows < 0) return fail(GCN_EINVAL, "gcn_halo_gather: negative size");
+  if (d < 1 || ld < d || ldr < d) return fail(GCN_EINVAL, "gcn_halo_gather: need 1 <= d <= ld, ldr");
+  if (dtype != GCN_F32 && dtype != GCN_BF16) return fail(GCN_EINVAL, "gcn_halo_gather: unknown dtype");
+  if (n_idx == 0) return GCN_OK;
+  if (!table || !d_idx || !recv) return fail(GCN_EINVAL, "gcn_halo_gather: NULL pointer");
+  if (n_idx > 0x7fffffffLL * 4) return fail(GCN_EINVAL, "gcn_halo_gather: index list too long");
+  const int64_t es = dtype == GCN_BF16 ? 2 : 4;
+  const int64_t row_bytes = d * es, ldb = ld * es, ldrb = ldr * es;
+  int vb = 16;
+  while (vb > es && !((row_bytes % vb) == 0 && (ldb % vb) == 0 && (ldrb % vb) == 0 &&
+                      ((uintptr_t)table % vb) == 0 && ((uintptr_t)recv % vb) == 0)) vb >>= 1;
+  const int n_vec = (int)(row_bytes / vb);
+  hipStream_t s = (hipStream_t)stream;
+  switch (vb) {
+    case 16: return gather_v<16>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, s);
+    case 8: return gather_v<8>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, s);
+    case 4: return gather_v<4>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, s);
+    default: return gather_v<2>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, s);
+  }
+}
+
+extern "C" int gcn_softmax_xent(const void* Z, int64_t ldz, int64_t nr, int C, int dtype, const int32_t* y,
+                                float scale, float* loss, void* G, int64_t ldg, void* stream) {
+  clear_error();
+  if (nr < 0 || C < 1) return fail(GCN_EINVAL, "gcn_softmax_xent: need nr >= 0 and C >= 1");
+  if (ldz < C || ldg < C) return fail(GCN_EINVAL, "gcn_softmax_xent: leading dimension smaller than C");
+  if (dtype != GCN_F32 && dtype != GCN_BF16) return fail(GCN_EINVAL, "gcn_softmax_xent: unknown dtype");
+  if (!loss || (nr > 0 && (!Z || !y || !G))) return fail(GCN_EINVAL, "gcn_softmax_xent: NULL pointer");
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype == GCN_BF16)
+    return softmax_t<bf16_t>((const bf16_t*)Z, ldz, nr, C, y, scale, loss, (bf16_t*)G, ldg, s);
+  return softmax_t<float>((const float*)Z, ldz, nr, C, y, scale, loss, (float*)G, ldg, s);
+}
