@@ -103,6 +103,9 @@ struct SpmmArgs {
   void* Y; int64_t ldy;      // epilogue result
   void* Y2; int64_t ldy2;    // optional second output: the value before ReLU (may be null)
   int d; int dtype; int epilogue; const float* bias; const void* Zprev; int64_t ldz;
+  // true when every row of X, the last one included, is backed by ldx readable elements (library
+  // buffers with a padded leading dimension): vector loads may then run past column d
+  bool x_rows_padded = false;
 };
 // ws: workspace for hub partial sums, at least spmm_ws_bytes(sched, d)
 size_t spmm_ws_bytes(const Schedule* sc, int d);

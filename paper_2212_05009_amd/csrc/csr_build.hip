@@ -135,8 +135,11 @@ __global__ void k_row_lengths(const int64_t* __restrict__ ptr, int64_t n, int32_
 
 // ---- step 5: values ---------------------------------------------------------------------------------
 // val(i,j) = fl(1/sqrt(d_i)) * fl(1/sqrt(d_j)), each operation correctly rounded in fp32.
+// Both steps go through fp64: an fp64 square root or quotient rounded once more to fp32 equals the
+// correctly rounded fp32 result (53 >= 2*24 + 2 bits), whatever the fp32 code generation options are.
 __device__ __forceinline__ float inv_sqrt_deg(int32_t d) {
-  return __fdiv_rn(1.0f, __fsqrt_rn((float)d));
+  const float r = (float)sqrt((double)(float)d);
+  return (float)(1.0 / (double)r);
 }
 
 __global__ void k_values(const uint64_t* __restrict__ ukeys, int64_t nnz, int colbits, int64_t nr,

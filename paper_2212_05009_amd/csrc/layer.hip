@@ -61,6 +61,7 @@ extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
         GCN_TRY(gemm_nn(H, ldh, W, d_out, P, ldp, A->nc, d_out, d_in, dtype, epi, s));
         SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nr, P, ldp, Hout, d_out, Z, d_out,
                     d_out, dtype, relu ? GCN_EPI_RELU : GCN_EPI_NONE, bias, nullptr, 0};
+        sp.x_rows_padded = true;
         GCN_TRY(spmm_launch(sp, hub, s));
       }
     }
@@ -124,6 +125,7 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
           GCN_TRY(gemm_nn(G, d_out, Wt, d_in, Q, ldq, A->nr, d_in, d_out, dtype, epi, s));
           SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, Q, ldq, dH, d_in, nullptr, 0,
                       d_in, dtype, Zprev ? GCN_EPI_MASK : GCN_EPI_NONE, nullptr, Zprev, d_in};
+          sp.x_rows_padded = true;
           GCN_TRY(spmm_launch(sp, hub, s));
         }
         const void* ah = AH_saved; int64_t ldah = d_in;

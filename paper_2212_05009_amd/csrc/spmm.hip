@@ -249,7 +249,8 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
   const size_t es = a.dtype == GCN_BF16 ? 2 : 4;
   // widest vector such that every feature row start stays aligned to it
   int V = a.dtype == GCN_BF16 ? 8 : 4;
-  while (V > 1 && !((a.ldx % V) == 0 && (a.ldy % V) == 0 && aligned(a.X, V * es) && aligned(a.Y, V * es))) V >>= 1;
+  while (V > 1 && !((a.ldx % V) == 0 && (a.ldy % V) == 0 && aligned(a.X, V * es) && aligned(a.Y, V * es) &&
+                    ((a.d % V) == 0 || a.x_rows_padded))) V >>= 1;
   if (a.dtype == GCN_BF16) {
     switch (V) {
       case 8: return launch_v<bf16_t, 8>(k, s);

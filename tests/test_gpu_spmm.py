@@ -1,0 +1,236 @@
+"""GPU parity: gcn_spmm, gcn_spmm_t and gcn_halo_gather against the oracle.
+
+Tolerance (written here as the contract): every output element must satisfy
+|gpu - oracle_fp64| <= 1e-5 * sum_j |A(i,j)| |X(j,c)| for fp32 features and 2e-2 * the same sum for
+bf16 features (both sides read the same bf16-rounded inputs).  The gather is a copy: bit-exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from util import TOL_BF16, TOL_F32, bf16_round, check_bound, hub_graph, say, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gcn():
+    import paper_2212_05009_amd as g
+    return g
+
+
+@pytest.fixture(scope="module")
+def dev():
+    import torch
+    assert torch.cuda.is_available()
+    return torch.device("cuda:0")
+
+
+class Case:
+    """A graph built on both sides once, reused by several tests."""
+
+    def __init__(self, gcn, dev, src, dst, n, lo=0, hi=None, deg_global=None):
+        import torch
+        self.og = oracle.graph_build(src, dst, n, lo, n if hi is None else hi, deg_global=deg_global)
+        dg = None if deg_global is None else torch.from_numpy(np.ascontiguousarray(deg_global, np.int32)).to(dev)
+        self.A = gcn.gcn_csr_build(torch.from_numpy(np.ascontiguousarray(src, np.int32)).to(dev),
+                                   torch.from_numpy(np.ascontiguousarray(dst, np.int32)).to(dev), n, lo,
+                                   n if hi is None else hi, deg_global=dg)
+
+
+@pytest.fixture(scope="module")
+def er(gcn, dev, c1):
+    return Case(gcn, dev, c1["src"], c1["dst"], c1["n"])
+
+
+@pytest.fixture(scope="module")
+def hubs(gcn, dev):
+    src, dst = hub_graph(9000, 3, 6.0, seed=5)       # rows of 9000, 4500 and 3000 entries: chunked path
+    return Case(gcn, dev, src, dst, 9000)
+
+
+@pytest.fixture(scope="module")
+def directed_block(gcn, dev):
+    rng = np.random.default_rng(17)
+    n, m = 6000, 90000
+    src = rng.integers(0, n, m); dst = rng.integers(0, n, m)
+    whole = oracle.graph_build(src, dst, n)
+    return Case(gcn, dev, src, dst, n, 1000, 3500, deg_global=whole.deg)
+
+
+def run_spmm(gcn, dev, case, d, bf16=False, transpose=False, epilogue="none", pad=0, seed=0, bias=False):
+    import torch
+    og, A = case.og, case.A
+    rng = np.random.default_rng(1000 + seed + d)
+    n_in, n_out = (og.nr, og.nc) if transpose else (og.nc, og.nr)
+    X = rng.standard_normal((n_in, d)).astype(np.float32)
+    if bf16:
+        X = bf16_round(X)
+    ptr, idx, val = (og.colptr, og.rowidx, og.val_t) if transpose else (og.rowptr, og.col, og.val)
+    ref, bound = oracle.spmm(ptr, idx, val, X)
+    b = None
+    if bias:
+        b = rng.standard_normal(d).astype(np.float32)
+        ref = ref + b.astype(np.float64); bound = bound + np.abs(b.astype(np.float64))
+    Zp = None
+    if epilogue == "relu":
+        ref = np.maximum(ref, 0.0)
+    elif epilogue == "mask":
+        Zp = rng.standard_normal((og.nr, d)).astype(np.float32)
+        if bf16:
+            Zp = bf16_round(Zp)
+        ref = ref.copy()
+        ref[: og.nr][~(Zp > 0)] = 0.0
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    Xd_full = torch.zeros(n_in, d + pad, dtype=tdt, device=dev)
+    Xd_full[:, :d] = to_dev(X, dev, bf16)
+    Yd_full = torch.full((n_out, d + pad), float("nan"), dtype=tdt, device=dev)
+    Xd, Yd = Xd_full[:, :d], Yd_full[:, :d]
+    code = {"none": gcn.EPI_NONE, "relu": gcn.EPI_RELU, "mask": gcn.EPI_MASK}[epilogue]
+    Zd = None if Zp is None else to_dev(Zp, dev, bf16)
+    say(f"spmm{'_t' if transpose else ''} rows={n_out} nnz={og.nnz} d={d} bf16={bf16} epi={epilogue} pad={pad} bias={bias}")
+    if transpose:
+        gcn.gcn_spmm_t(A, Xd, Yd, epilogue=code, Zprev=Zd)
+    else:
+        gcn.gcn_spmm(A, Xd, Yd, epilogue=code, bias=None if b is None else to_dev(b, dev), Zprev=Zd)
+    torch.cuda.synchronize()
+    got = to_np(Yd)
+    tol = TOL_BF16 if bf16 else TOL_F32
+    if epilogue == "relu":
+        # a value the oracle sees at +-tiny may land on the other side of zero: both are within the bound
+        pass
+    r = check_bound(got, ref, bound, tol, what=f"spmm d={d}")
+    if pad:
+        assert bool(torch.isnan(Yd_full[:, d:].float()).all()), "wrote outside the d columns"
+    return r
+
+
+@pytest.mark.parametrize("d", [1, 2, 3, 8, 16, 41, 47, 64, 100, 128, 130, 256, 602])
+def test_spmm_widths_fp32(gcn, dev, er, d):
+    run_spmm(gcn, dev, er, d)
+
+
+@pytest.mark.parametrize("d", [1, 7, 16, 41, 64, 100, 128, 256, 602])
+def test_spmm_widths_bf16(gcn, dev, er, d):
+    run_spmm(gcn, dev, er, d, bf16=True)
+
+
+@pytest.mark.parametrize("d,pad", [(16, 1), (41, 3), (128, 2), (100, 4), (64, 8)])
+def test_spmm_padded_leading_dimension(gcn, dev, er, d, pad):
+    run_spmm(gcn, dev, er, d, pad=pad)
+    run_spmm(gcn, dev, er, d, pad=pad, bf16=True)
+
+
+@pytest.mark.parametrize("epilogue", ["relu", "mask"])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_spmm_epilogues(gcn, dev, er, epilogue, bf16):
+    run_spmm(gcn, dev, er, 48, bf16=bf16, epilogue=epilogue)
+    run_spmm(gcn, dev, er, 128, bf16=bf16, epilogue=epilogue, bias=(epilogue == "relu"))
+
+
+@pytest.mark.parametrize("d", [1, 16, 47, 128, 602])
+def test_spmm_hub_rows(gcn, dev, hubs, d):
+    assert hubs.og.deg.max() > 2048
+    run_spmm(gcn, dev, hubs, d)
+    run_spmm(gcn, dev, hubs, d, transpose=True, epilogue="mask")
+    run_spmm(gcn, dev, hubs, d, bf16=True, epilogue="relu")
+
+
+@pytest.mark.parametrize("d", [5, 64, 100])
+def test_spmm_t_directed_block(gcn, dev, directed_block, d):
+    og = directed_block.og
+    assert og.nh > 0 and not np.array_equal(og.colptr[: og.nr + 1], og.rowptr)
+    run_spmm(gcn, dev, directed_block, d)
+    run_spmm(gcn, dev, directed_block, d, transpose=True)
+    run_spmm(gcn, dev, directed_block, d, transpose=True, epilogue="mask")
+    run_spmm(gcn, dev, directed_block, d, transpose=True, bf16=True)
+
+
+def test_spmm_is_run_to_run_identical(gcn, dev, hubs):
+    import torch
+    X = torch.randn(hubs.og.nc, 96, device=dev)
+    Y1 = torch.empty(hubs.og.nr, 96, device=dev); Y2 = torch.empty_like(Y1)
+    gcn.gcn_spmm(hubs.A, X, Y1); gcn.gcn_spmm(hubs.A, X, Y2)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2)
+
+
+def test_spmm_argument_errors(gcn, dev, er):
+    import torch
+    X = torch.zeros(er.og.nc, 8, device=dev); Y = torch.zeros(er.og.nr, 8, device=dev)
+    with pytest.raises(TypeError):
+        gcn.gcn_spmm(er.A, X[:-1], Y)
+    with pytest.raises(gcn.GcnError):
+        gcn.gcn_spmm(er.A, X, Y, epilogue=gcn.EPI_MASK)          # mask without Zprev
+    with pytest.raises(gcn.GcnError):
+        gcn.gcn_spmm(er.A, X, Y, epilogue=7)
+
+
+# ----------------------------------------------------------------------------- gather
+@pytest.mark.parametrize("d", [1, 3, 32, 100, 128, 602])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_gather_device_table(gcn, dev, d, bf16):
+    import torch
+    rng = np.random.default_rng(d)
+    T = rng.standard_normal((3000, d)).astype(np.float32)
+    if bf16:
+        T = bf16_round(T)
+    idx = rng.integers(0, 3000, 7777).astype(np.int32)
+    want = oracle.gather(T, idx)
+    Td = to_dev(T, dev, bf16)
+    recv = torch.empty(idx.size, d, dtype=Td.dtype, device=dev)
+    say(f"gather device d={d} bf16={bf16}")
+    gcn.gcn_halo_gather(Td, to_dev(idx, dev), recv)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(recv).view(np.int32), want.view(np.int32))
+
+
+def test_gather_pinned_host_table_and_edge_cases(gcn, dev):
+    import torch
+    rng = np.random.default_rng(4)
+    T = rng.standard_normal((5000, 128)).astype(np.float32)
+    Th = torch.from_numpy(T).pin_memory()
+    idx = rng.integers(0, 5000, 4001).astype(np.int32)
+    recv = torch.empty(idx.size, 128, device=dev)
+    say("gather pinned host table")
+    gcn.gcn_halo_gather(Th, to_dev(idx, dev), recv)
+    torch.cuda.synchronize()
+    assert np.array_equal(recv.cpu().numpy(), oracle.gather(T, idx))
+    # identity list returns the table; empty list is a no-op; an out-of-range id gives a zero row
+    Td = to_dev(T, dev)
+    recv = torch.empty(5000, 128, device=dev)
+    gcn.gcn_halo_gather(Td, to_dev(np.arange(5000, dtype=np.int32), dev), recv)
+    assert torch.equal(recv, Td)
+    gcn.gcn_halo_gather(Td, torch.zeros(0, dtype=torch.int32, device=dev), torch.empty(0, 128, device=dev))
+    bad = to_dev(np.array([1, 5000, -1, 2], np.int32), dev)
+    recv = torch.full((4, 128), 7.0, device=dev)
+    gcn.gcn_halo_gather(Td, bad, recv)
+    torch.cuda.synchronize()
+    assert torch.equal(recv[0], Td[1]) and torch.equal(recv[3], Td[2])
+    assert float(recv[1].abs().sum()) == 0.0 and float(recv[2].abs().sum()) == 0.0
+    # padded rows on both sides
+    Tp = torch.zeros(5000, 131, device=dev); Tp[:, :128] = Td
+    Rp = torch.full((idx.size, 130), -1.0, device=dev)
+    gcn.gcn_halo_gather(Tp[:, :128], to_dev(idx, dev), Rp[:, :128])
+    torch.cuda.synchronize()
+    assert np.array_equal(Rp[:, :128].cpu().numpy(), oracle.gather(T, idx)) and bool((Rp[:, 128:] == -1).all())
+
+
+def test_gather_halo_rows_of_a_block_feed_the_block_product(gcn, dev, directed_block):
+    """Sec. 4.1 block form: owned rows + rows fetched through the halo list reproduce the rows of A X."""
+    import torch
+    og, A = directed_block.og, directed_block.A
+    rng = np.random.default_rng(8)
+    n, d, lo = 6000, 64, 1000
+    Xg = rng.standard_normal((n, d)).astype(np.float32)
+    Xd = to_dev(Xg, dev)
+    Hb = torch.empty(og.nc, d, device=dev)
+    Hb[: og.nr] = Xd[lo: lo + og.nr]
+    gcn.gcn_halo_gather(Xd, A.arrays()["halo_gid"], Hb[og.nr:])
+    Y = torch.empty(og.nr, d, device=dev)
+    gcn.gcn_spmm(A, Hb, Y)
+    torch.cuda.synchronize()
+    Xb = np.concatenate([Xg[lo: lo + og.nr], Xg[og.halo_gid]])
+    assert np.array_equal(Hb.cpu().numpy(), Xb)
+    ref, bound = oracle.spmm(og.rowptr, og.col, og.val, Xb)
+    check_bound(Y.cpu().numpy(), ref, bound, TOL_F32, "block product")
