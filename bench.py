@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the full-batch GCN epoch (forward, loss, backward over all layers) on one MI355X.
+
+One "step" is one epoch over one seeded synthetic graph, with graph, features and weights already
+resident in HBM; the CSR/CSC build is set-up and is reported separately.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_rmat18] [--dtype f32|bf16]
+                    [--no-cpu-baseline] [--cpu-sample-frac F]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+class Epoch:
+    """Buffers and call sequence of one epoch; every step is a call into the C-ABI library."""
+
+    def __init__(self, gcn, torch, A, X, Ws, y, bf16):
+        self.gcn, self.torch, self.A, self.X, self.Ws, self.y = gcn, torch, A, X, Ws, y
+        dev = X.device
+        fdt = torch.bfloat16 if bf16 else torch.float32
+        dims = [X.shape[1]] + [W.shape[1] for W in Ws]
+        self.dims, self.L, nr = dims, len(Ws), A.nr
+        assert A.nh == 0, "whole-graph epoch"
+        # activations H[k] (input of layer k), pre-activations Z[k], gradients G[k] w.r.t. Z[k]
+        self.H = [X] + [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L - 1)]
+        self.Z = [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L)]
+        self.G = [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L)]
+        # A^ H is kept for the weight gradient where the forward pass computes it anyway
+        self.AH = [torch.empty(nr, dims[k], dtype=fdt, device=dev) if dims[k] <= dims[k + 1] else None
+                   for k in range(self.L)]
+        self.dW = [torch.empty_like(W) for W in Ws]
+        self.loss = torch.zeros(1, device=dev)
+
+    def run(self):
+        g, A, L = self.gcn, self.A, self.L
+        for k in range(L):
+            last = k == L - 1
+            out = self.Z[k] if last else self.H[k + 1]
+            g.gcn_layer_fwd(A, self.H[k], self.Ws[k], out, act=g.ACT_NONE if last else g.ACT_RELU,
+                            Z=None if last else self.Z[k], AH_save=self.AH[k])
+        g.gcn_softmax_xent(self.Z[L - 1], self.y, 1.0 / A.nr, self.loss, self.G[L - 1])
+        for k in range(L - 1, -1, -1):
+            g.gcn_layer_bwd(A, self.H[k], self.Ws[k], self.G[k], self.dW[k],
+                            dH=self.G[k - 1] if k > 0 else None, Zprev=self.Z[k - 1] if k > 0 else None,
+                            AH_saved=self.AH[k])
+
+
+def cpu_baseline(w, frac):
+    """Time the oracle, as it stands, on one epoch over the row block [0, frac*n) of the same graph."""
+    import numpy as np
+    import oracle
+    from workloads import configs
+    n, dims = w["n"], w["dims"]
+    hi = max(1, int(n * frac))
+    t0 = time.time()
+    whole = oracle.graph_build(w["src"], w["dst"], n)
+    blk = oracle.graph_build(w["src"], w["dst"], n, 0, hi, deg_global=whole.deg)
+    log(f"oracle graphs built in {time.time() - t0:.1f}s: block rows={blk.nr} halo={blk.nh} nnz={blk.nnz} of {whole.nnz}")
+    L = len(dims) - 1
+    Hs = [configs.features(blk.nc, dims[k], 900 + k) for k in range(L)]
+    Zp = [configs.features(blk.nr, dims[k], 950 + k) for k in range(L)]
+    t0 = time.time()
+    for k in range(L):
+        oracle.layer_fwd(blk, Hs[k], w["W"][k], act="none" if k == L - 1 else "relu")
+    _, _, G = oracle.softmax_xent(configs.features(blk.nr, dims[L], 990), w["y"][:hi], 1.0 / hi)
+    G = G.astype(np.float32)
+    for k in range(L - 1, -1, -1):
+        b = oracle.layer_bwd(blk, Hs[k], w["W"][k], G, Zprev=Zp[k] if k > 0 else None, want_dH=k > 0)
+        if k > 0:
+            G = b["dH"][: blk.nr].astype(np.float32)
+    sec = time.time() - t0
+    scale = whole.nnz / blk.nnz
+    return {"value": sec * 1e3 * scale, "unit": "ms/epoch", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"one epoch (all layers forward, loss, backward; fp64, with bound sums) on the row block "
+                      f"[0,{hi}) of the same graph ({blk.nnz} of {whole.nnz} stored entries, halo {blk.nh} rows) took "
+                      f"{sec:.2f}s; value = that time x {scale:.2f} (ratio of stored entries)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2_rmat18")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-frac", type=float, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the row block of one processor); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2212_05009_amd as gcn      # raises if the HIP library is missing: there is no fallback
+    from workloads import configs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    bf16 = args.dtype == "bf16"
+
+    t0 = time.time()
+    w = configs.get(args.workload)
+    n, dims = w["n"], w["dims"]
+    log(f"workload {args.workload}: n={n} raw directed edges={w['src'].size} dims={dims} generated in {time.time() - t0:.1f}s")
+
+    src, dst = torch.from_numpy(w["src"]).to(dev), torch.from_numpy(w["dst"]).to(dev)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    A = gcn.gcn_csr_build(src, dst, n)
+    torch.cuda.synchronize()
+    build_ms = (time.time() - t0) * 1e3
+    del src, dst
+    log(f"csr+csc build: {build_ms:.1f} ms, nnz={A.nnz}")
+
+    X = torch.from_numpy(w["X"]).to(dev)
+    if bf16:
+        X = X.to(torch.bfloat16)
+    Ws = [torch.from_numpy(m).to(dev) for m in w["W"]]
+    y = torch.from_numpy(w["y"]).to(dev)
+    ep = Epoch(gcn, torch, A, X, Ws, y, bf16)
+
+    for _ in range(args.warmup):
+        ep.run()
+    torch.cuda.synchronize()
+    gcn.gcn_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ep.run()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    gcn.gcn_profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    loss = float(ep.loss.item())
+    log(f"{ms_per_step:.3f} ms/epoch, loss={loss:.5f}")
+
+    recs, dropped = gcn.gcn_profile_records()
+    groups = {}
+    for r in recs:
+        key = (r["kind"], r["d"], r["rows"], r["inner"])
+        q = groups.setdefault(key, {"kind": r["kind"], "d": r["d"], "rows": r["rows"], "inner": r["inner"], "launches": 0,
+                                    "ms": 0.0, "alg_bytes": r["alg_bytes"], "touched_bytes": r["touched_bytes"],
+                                    "flops": r["flops"]})
+        q["launches"] += 1
+        q["ms"] += r["ms"]
+    kernels = []
+    for q in groups.values():
+        avg = q["ms"] / q["launches"]
+        kernels.append({"kind": q["kind"], "d": q["d"], "rows": q["rows"], "inner": q["inner"],
+                        "launches_per_step": q["launches"] / args.steps, "avg_ms": round(avg, 5),
+                        "ms_per_step": round(q["ms"] / args.steps, 5),
+                        "alg_GBps": round(q["alg_bytes"] / avg / 1e6, 2) if avg > 0 else None,
+                        "touched_GBps": round(q["touched_bytes"] / avg / 1e6, 2) if avg > 0 else None,
+                        "TFLOPps": round(q["flops"] / avg / 1e9, 3) if avg > 0 else None})
+    kernels.sort(key=lambda k: -k["ms_per_step"])
+    dom = kernels[0]
+    is_gemm = dom["kind"].startswith("gemm_") and dom["kind"] != "gemm_tn_sum"
+    intensity = (dom["TFLOPps"] or 0) * 1e3 / max(dom["alg_GBps"] or 1e-9, 1e-9)      # flop per byte
+    if is_gemm and intensity > MFMA_PEAK_TFLOPS[args.dtype] * 1e3 / HBM_PEAK_GBS:
+        roof = {"bound": "mfma", "achieved": dom["TFLOPps"], "peak": MFMA_PEAK_TFLOPS[args.dtype], "unit": "TFLOP/s",
+                "frac": round(dom["TFLOPps"] / MFMA_PEAK_TFLOPS[args.dtype], 4), "traffic": None}
+    else:
+        roof = {"bound": "hbm", "achieved": dom["alg_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(dom["alg_GBps"] / HBM_PEAK_GBS, 4), "traffic": None}
+    roof["kernel"] = f"{dom['kind']} d={dom['d']} rows={dom['rows']} inner={dom['inner']}"
+    roof["avg_launch_ms"] = dom["avg_ms"]
+    roof["touched_GBps"] = dom["touched_GBps"]
+
+    out = {"metric": "GCN full-batch epoch ms (fwd+bwd) on 1 MI355X", "value": round(ms_per_step, 4), "unit": "ms/epoch",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+           "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+           "config": {"workload": args.workload, "n": n, "nnz": A.nnz, "dims": dims, "layers": len(dims) - 1},
+           "epochs_per_s": round(1e3 / ms_per_step, 2), "loss": round(loss, 6), "csr_csc_build_ms": round(build_ms, 2),
+           "roofline": roof, "kernels": kernels, "profile_records_dropped": dropped}
+    if not args.no_cpu_baseline:
+        frac = args.cpu_sample_frac
+        if frac is None:
+            frac = min(1.0, 4.0e6 / max(A.nnz, 1))          # about 4 M stored entries of oracle work
+        out["cpu_baseline"] = cpu_baseline(w, frac)
+    A.free()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

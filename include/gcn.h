@@ -182,6 +182,47 @@ int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, const void* AH
 int gcn_softmax_xent(const void* Z, int64_t ldz, int64_t nr, int C, int dtype, const int32_t* y,
                      float scale, float* loss, void* G, int64_t ldg, void* stream);
 
+/*
+ * Per-kernel timing, for benchmarks (instrumentation; no part of the paper's method).
+ * While enabled, every kernel launch of the library is bracketed by a pair of HIP events recorded
+ * on the stream the kernel is launched on, and described by one record.  Records are kept in
+ * launch order up to a fixed capacity (65536); later launches run untimed and are counted as
+ * dropped.  gcn_profile_enable(1) clears the records and starts recording, gcn_profile_enable(0)
+ * stops.  gcn_profile_get synchronises with the record's stop event.
+ *
+ *   kind       GCN_K_* below.
+ *   d          feature width of the launch (N of a dense product, C of the loss).
+ *   rows       output rows (sparse products, gather, loss) or M of a dense product.
+ *   inner      stored entries of the sparse matrix, or the reduction length K of a dense product.
+ *   alg_bytes  bytes the operation has to move at least once: every operand and result once
+ *              (sparse products: 8 bytes per stored entry + 8 per row pointer + each feature row
+ *              of the input and of the output once).
+ *   touched_bytes  sparse products only: as alg_bytes, but a gathered feature row is counted every
+ *              time it is read (what caches and HBM together serve); else equal to alg_bytes.
+ *   flops      2 * multiply-adds.
+ *   ms         elapsed time between the two events.
+ */
+#define GCN_K_SPMM 0          /* A X, main kernel */
+#define GCN_K_SPMM_T 1        /* A^T X, main kernel */
+#define GCN_K_SPMM_FINISH 2   /* sum of the partial rows of long rows + epilogue */
+#define GCN_K_GEMM_NN 3
+#define GCN_K_GEMM_TN 4       /* partial tiles of A^T B */
+#define GCN_K_GEMM_TN_SUM 5   /* sum of the partial tiles */
+#define GCN_K_SOFTMAX_XENT 6
+#define GCN_K_GATHER 7
+#define GCN_K_OTHER 8         /* small helpers: weight transpose, column sums, loss finish */
+
+typedef struct {
+  int32_t kind, d, dtype, reserved;
+  int64_t rows, inner;
+  double alg_bytes, touched_bytes, flops, ms;
+} gcn_profile_rec;
+
+int gcn_profile_enable(int on);
+/* number of records held; *dropped (may be NULL) = launches not recorded for lack of capacity */
+int64_t gcn_profile_count(int64_t* dropped);
+int gcn_profile_get(int64_t i, gcn_profile_rec* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,16 @@ class GcnError(RuntimeError):
     pass
 
 
+class ProfileRec(C.Structure):
+    """Mirror of gcn_profile_rec."""
+    _fields_ = [("kind", C.c_int32), ("d", C.c_int32), ("dtype", C.c_int32), ("reserved", C.c_int32),
+                ("rows", C.c_int64), ("inner", C.c_int64), ("alg_bytes", C.c_double),
+                ("touched_bytes", C.c_double), ("flops", C.c_double), ("ms", C.c_double)]
+
+
+KIND_NAMES = ["spmm", "spmm_t", "spmm_finish", "gemm_nn", "gemm_tn", "gemm_tn_sum", "softmax_xent", "gather", "other"]
+
+
 def library_path() -> str:
     return _LIB_PATH
 
@@ -42,6 +52,12 @@ def _load():
     lib.gcn_layer_fwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]
     lib.gcn_layer_bwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.gcn_softmax_xent.argtypes = [vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, C.c_float, vp, vp, C.c_int64, vp]
+    lib.gcn_profile_enable.argtypes = [C.c_int]
+    lib.gcn_profile_enable.restype = C.c_int
+    lib.gcn_profile_count.argtypes = [i64p]
+    lib.gcn_profile_count.restype = C.c_int64
+    lib.gcn_profile_get.argtypes = [C.c_int64, C.POINTER(ProfileRec)]
+    lib.gcn_profile_get.restype = C.c_int
     for name in ("gcn_csr_build", "gcn_csr_info", "gcn_csr_arrays", "gcn_csr_free", "gcn_spmm", "gcn_spmm_t",
                  "gcn_halo_gather", "gcn_layer_fwd", "gcn_layer_bwd", "gcn_softmax_xent"):
         getattr(lib, name).restype = C.c_int
@@ -263,3 +279,20 @@ def gcn_softmax_xent(Z: torch.Tensor, y: torch.Tensor, scale: float, loss: torch
     _check(_lib.gcn_softmax_xent(_ptr(Z), ldz, Z.shape[0], Cn, _dtype_code(Z), _ptr(y), float(scale), _ptr(loss),
                                  _ptr(G), ldg, _stream()), "gcn_softmax_xent")
     return loss
+
+
+def gcn_profile_enable(on: bool):
+    _check(_lib.gcn_profile_enable(1 if on else 0), "gcn_profile_enable")
+
+
+def gcn_profile_records():
+    """All records held by the library, as dicts (synchronises with each record's stop event)."""
+    dropped = C.c_int64()
+    n = _lib.gcn_profile_count(C.byref(dropped))
+    out = []
+    rec = ProfileRec()
+    for i in range(n):
+        _check(_lib.gcn_profile_get(i, C.byref(rec)), "gcn_profile_get")
+        out.append({"kind": KIND_NAMES[rec.kind], "d": rec.d, "dtype": rec.dtype, "rows": rec.rows, "inner": rec.inner,
+                    "alg_bytes": rec.alg_bytes, "touched_bytes": rec.touched_bytes, "flops": rec.flops, "ms": rec.ms})
+    return out, dropped.value

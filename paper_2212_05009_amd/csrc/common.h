@@ -27,6 +27,20 @@ void clear_error();
 
 #define GCN_CHECK_LAUNCH() GCN_HIP(hipGetLastError())
 
+// ---- optional per-kernel timing (profile.hip) ------------------------------------------------
+// Put one on the stack around a kernel launch: records a start event now and a stop event when it
+// goes out of scope, both on `s`, if profiling is enabled; otherwise costs one relaxed load.
+struct ProfScope {
+  ProfScope(int kind, hipStream_t s, int d, int dtype, int64_t rows, int64_t inner, double alg_bytes,
+            double touched_bytes, double flops);
+  ~ProfScope();
+  ProfScope(const ProfScope&) = delete;
+  ProfScope& operator=(const ProfScope&) = delete;
+ private:
+  int64_t slot_ = -1;
+  hipStream_t s_;
+};
+
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 
@@ -98,6 +112,9 @@ void free_schedule(Schedule* sc);
 struct SpmmArgs {
   const int64_t* ptr; const int32_t* idx; const float* val; const Schedule* sched;
   int64_t n_rows;            // rows of the sparse matrix (= rows of Y)
+  int64_t n_cols;            // columns of the sparse matrix (= rows of X)
+  int64_t nnz;               // stored entries
+  bool transposed;           // the arrays are the column-major copy (only labels the profile record)
   int64_t n_mask_rows;       // rows covered by bias / relu / mask epilogues that need Zprev
   const void* X; int64_t ldx;
   void* Y; int64_t ldy;      // epilogue result

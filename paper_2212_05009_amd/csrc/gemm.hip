@@ -190,6 +190,10 @@ template <typename T>
 static int gemm_nn_t(NnArgs& a, hipStream_t s) {
   const int64_t gm = ceil_div(a.M, BM);
   if (gm > 0x7fffffffLL) return fail(GCN_EINVAL, "gemm: too many rows");
+  const double nb = (double)sizeof(T) * (double)a.M * (a.K + a.N * (a.C2 ? 2.0 : 1.0) + (a.mask ? a.N : 0)) +
+                    4.0 * (double)a.K * a.N;
+  ProfScope ps(GCN_K_GEMM_NN, s, a.N, sizeof(T) == 2 ? GCN_BF16 : GCN_F32, a.M, a.K, nb, nb,
+               2.0 * (double)a.M * a.N * a.K);
   if (a.N <= 32) {
     k_gemm_nn<T, 32, 4, 1><<<dim3((unsigned)gm, (unsigned)ceil_div(a.N, 32)), 256, 0, s>>>(a);
   } else if (a.N <= 64) {
@@ -339,10 +343,18 @@ int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, in
   a.nsplit = tn_splits(Kd, M, N);
   a.rows_per_split = round_up(ceil_div(Kd > 0 ? Kd : 1, a.nsplit), BK);
   dim3 grid((unsigned)a.nsplit, (unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, TN_BN));
-  if (dtype == GCN_BF16) k_gemm_tn<bf16_t><<<grid, 256, 0, s>>>(a);
-  else k_gemm_tn<float><<<grid, 256, 0, s>>>(a);
   const int64_t mn = (int64_t)M * N;
-  k_tn_reduce<<<(unsigned)ceil_div(mn, 256), 256, 0, s>>>(a.partial, a.nsplit, mn, N, C, ldc);
+  {
+    const double nb = (double)es * (double)Kd * (M + N) + 4.0 * (double)mn;
+    ProfScope ps(GCN_K_GEMM_TN, s, N, dtype, M, Kd, nb, nb, 2.0 * (double)Kd * M * N);
+    if (dtype == GCN_BF16) k_gemm_tn<bf16_t><<<grid, 256, 0, s>>>(a);
+    else k_gemm_tn<float><<<grid, 256, 0, s>>>(a);
+  }
+  {
+    const double nb = 4.0 * (double)mn * (a.nsplit + 1);
+    ProfScope ps(GCN_K_GEMM_TN_SUM, s, N, GCN_F32, M, a.nsplit, nb, nb, (double)mn * a.nsplit);
+    k_tn_reduce<<<(unsigned)ceil_div(mn, 256), 256, 0, s>>>(a.partial, a.nsplit, mn, N, C, ldc);
+  }
   GCN_CHECK_LAUNCH();
   return GCN_OK;
 }
@@ -356,6 +368,7 @@ __global__ void k_transpose(const float* __restrict__ W, int K, int N, float* __
 }
 
 int transpose_f32(const float* W, int K, int N, float* Wt, hipStream_t s) {
+  ProfScope ps(GCN_K_OTHER, s, N, GCN_F32, K, 0, 8.0 * K * N, 8.0 * K * N, 0.0);
   k_transpose<<<(unsigned)ceil_div((int64_t)K * N, 256), 256, 0, s>>>(W, K, N, Wt);
   GCN_CHECK_LAUNCH();
   return GCN_OK;
@@ -394,6 +407,8 @@ __global__ void k_colsum_finish(const float* __restrict__ partial, int64_t nb, i
 size_t colsum_ws_bytes(int64_t rows, int N) { return sizeof(float) * (size_t)ceil_div(rows > 0 ? rows : 1, kColsumRows) * (size_t)N; }
 int colsum(const void* G, int64_t ldg, int64_t rows, int N, int dtype, float* out, void* ws, hipStream_t s) {
   const int64_t nb = ceil_div(rows > 0 ? rows : 1, kColsumRows);
+  const double by = (dtype == GCN_BF16 ? 2.0 : 4.0) * (double)rows * N;
+  ProfScope ps(GCN_K_OTHER, s, N, dtype, rows, 0, by, by, (double)rows * N);
   if (dtype == GCN_BF16) k_colsum_part<bf16_t><<<(unsigned)nb, 256, 0, s>>>((const bf16_t*)G, ldg, rows, N, (float*)ws);
   else k_colsum_part<float><<<(unsigned)nb, 256, 0, s>>>((const float*)G, ldg, rows, N, (float*)ws);
   k_colsum_finish<<<(unsigned)ceil_div(N, 256), 256, 0, s>>>((const float*)ws, nb, N, out);

@@ -46,7 +46,7 @@ extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
     if (sparse_first) {
       void* AH = AH_save ? AH_save : ws.take((size_t)A->nr * d_in * es);
       if (pass) {
-        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nr, H, ldh, AH, d_in, nullptr, 0,
+        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, H, ldh, AH, d_in, nullptr, 0,
                     d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
         GCN_TRY(spmm_launch(sp, hub, s));
         GemmEpilogue epi;
@@ -59,7 +59,7 @@ extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
       if (pass) {
         GemmEpilogue epi;
         GCN_TRY(gemm_nn(H, ldh, W, d_out, P, ldp, A->nc, d_out, d_in, dtype, epi, s));
-        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nr, P, ldp, Hout, d_out, Z, d_out,
+        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, P, ldp, Hout, d_out, Z, d_out,
                     d_out, dtype, relu ? GCN_EPI_RELU : GCN_EPI_NONE, bias, nullptr, 0};
         sp.x_rows_padded = true;
         GCN_TRY(spmm_launch(sp, hub, s));
@@ -101,7 +101,7 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
       const int64_t kd = AH_saved ? A->nr : A->nc;
       void* tn = ws.take(gemm_tn_ws_bytes(kd, d_in, d_out));
       if (pass) {
-        SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, G, d_out, T, ldt, nullptr, 0,
+        SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, G, d_out, T, ldt, nullptr, 0,
                     d_out, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
         GCN_TRY(spmm_launch(sp, hub, s));
         if (dH) {
@@ -123,14 +123,14 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
           GCN_TRY(transpose_f32(W, d_in, d_out, Wt, s));
           GemmEpilogue epi;
           GCN_TRY(gemm_nn(G, d_out, Wt, d_in, Q, ldq, A->nr, d_in, d_out, dtype, epi, s));
-          SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, Q, ldq, dH, d_in, nullptr, 0,
+          SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, Q, ldq, dH, d_in, nullptr, 0,
                       d_in, dtype, Zprev ? GCN_EPI_MASK : GCN_EPI_NONE, nullptr, Zprev, d_in};
           sp.x_rows_padded = true;
           GCN_TRY(spmm_launch(sp, hub, s));
         }
         const void* ah = AH_saved; int64_t ldah = d_in;
         if (!AH_saved) {
-          SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nr, H, ldh, AH, ldq, nullptr, 0,
+          SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, H, ldh, AH, ldq, nullptr, 0,
                       d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
           GCN_TRY(spmm_launch(sp, hub, s));
           ah = AH; ldah = ldq;

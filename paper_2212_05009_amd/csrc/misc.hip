@@ -54,8 +54,10 @@ __global__ __launch_bounds__(256) void k_gather(const char* __restrict__ table, 
 
 template <int VB>
 static int gather_v(const char* table, int64_t ldb, int64_t nt, int n_vec, const int32_t* idx, int64_t n_idx,
-                    char* recv, int64_t ldrb, hipStream_t s) {
+                    char* recv, int64_t ldrb, int d, int dtype, hipStream_t s) {
   auto grid = [&](int lpr) { return dim3((unsigned)ceil_div(n_idx, 256 / lpr)); };
+  const double by = 2.0 * (double)n_idx * n_vec * VB + 4.0 * (double)n_idx;
+  ProfScope ps(GCN_K_GATHER, s, d, dtype, n_idx, 0, by, by, 0.0);
   if (n_vec <= 4) k_gather<VB, 4><<<grid(4), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
   else if (n_vec <= 8) k_gather<VB, 8><<<grid(8), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
   else if (n_vec <= 16) k_gather<VB, 16><<<grid(16), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
@@ -142,6 +144,8 @@ static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* 
   while (lpr < 64 && lpr < C) lpr <<= 1;
   int64_t want = ceil_div(nr > 0 ? nr : 1, 256 / lpr);
   int nb = (int)(want < kLossBlocks ? want : kLossBlocks);
+  const double by = (double)nr * (2.0 * sizeof(T) * C + 4.0);
+  ProfScope ps(GCN_K_SOFTMAX_XENT, s, C, sizeof(T) == 2 ? GCN_BF16 : GCN_F32, nr, 0, by, by, 0.0);
   switch (lpr) {
     case 4: k_softmax_xent<T, 4><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
     case 8: k_softmax_xent<T, 8><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
@@ -177,10 +181,10 @@ extern "C" int gcn_halo_gather(const void* table, int64_t ld, int64_t n_table_ro
   const int n_vec = (int)(row_bytes / vb);
   hipStream_t s = (hipStream_t)stream;
   switch (vb) {
-    case 16: return gather_v<16>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, s);
-    case 8: return gather_v<8>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, s);
-    case 4: return gather_v<4>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, s);
-    default: return gather_v<2>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, s);
+    case 16: return gather_v<16>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, d, dtype, s);
+    case 8: return gather_v<8>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, d, dtype, s);
+    case 4: return gather_v<4>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, d, dtype, s);
+    default: return gather_v<2>((const char*)table, ldb, n_table_rows, n_vec, d_idx, n_idx, (char*)recv, ldrb, d, dtype, s);
   }
 }
 

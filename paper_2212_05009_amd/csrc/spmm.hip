@@ -215,12 +215,15 @@ size_t spmm_ws_bytes(const Schedule* sc, int d) {
   return sizeof(float) * (size_t)(sc->n_chunks > 0 ? sc->n_chunks : 1) * (size_t)d;
 }
 
+struct SpmmProf { int kind; int dtype; int64_t rows, nnz; double alg, touched, flops; };
+
 template <typename T, int V>
-static int launch_v(const SpmmK& k, hipStream_t s) {
+static int launch_v(const SpmmK& k, const SpmmProf& pf, hipStream_t s) {
   const int per_row = (int)ceil_div(k.d, V);
   const int64_t blocks = k.n_chunks + ceil_div(k.n_wave_rows, 4);
   if (blocks > 0x7fffffffLL) return fail(GCN_EINVAL, "spmm: too many rows for one launch");
   if (blocks > 0) {
+    ProfScope ps(pf.kind, s, k.d, pf.dtype, pf.rows, pf.nnz, pf.alg, pf.touched, pf.flops);
     dim3 grid((unsigned)blocks), block(256);
     if (per_row <= 4) k_spmm<T, V, 4><<<grid, block, 0, s>>>(k);
     else if (per_row <= 8) k_spmm<T, V, 8><<<grid, block, 0, s>>>(k);
@@ -228,8 +231,11 @@ static int launch_v(const SpmmK& k, hipStream_t s) {
     else if (per_row <= 32) k_spmm<T, V, 32><<<grid, block, 0, s>>>(k);
     else k_spmm<T, V, 64><<<grid, block, 0, s>>>(k);
   }
-  if (k.n_hub_rows > 0)
+  if (k.n_hub_rows > 0) {
+    const double fb = 4.0 * (double)k.n_chunks * k.d + (double)sizeof(T) * (double)k.n_hub_rows * k.d;
+    ProfScope ps(GCN_K_SPMM_FINISH, s, k.d, pf.dtype, k.n_hub_rows, k.n_chunks, fb, fb, (double)k.n_chunks * k.d);
     k_spmm_hub_finish<T><<<dim3((unsigned)ceil_div(k.n_hub_rows, 4)), dim3(256), 0, s>>>(k);
+  }
   GCN_CHECK_LAUNCH();
   return GCN_OK;
 }
@@ -251,18 +257,24 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
   int V = a.dtype == GCN_BF16 ? 8 : 4;
   while (V > 1 && !((a.ldx % V) == 0 && (a.ldy % V) == 0 && aligned(a.X, V * es) && aligned(a.Y, V * es) &&
                     ((a.d % V) == 0 || a.x_rows_padded))) V >>= 1;
+  SpmmProf pf;
+  pf.kind = a.transposed ? GCN_K_SPMM_T : GCN_K_SPMM; pf.dtype = a.dtype; pf.rows = a.n_rows; pf.nnz = a.nnz;
+  const double csr = 8.0 * (double)a.nnz + 8.0 * (double)(a.n_rows + 1), fe = (double)es * a.d;
+  pf.alg = csr + fe * (double)(a.n_cols + a.n_rows);
+  pf.touched = csr + fe * (double)(a.nnz + a.n_rows);
+  pf.flops = 2.0 * (double)a.nnz * a.d;
   if (a.dtype == GCN_BF16) {
     switch (V) {
-      case 8: return launch_v<bf16_t, 8>(k, s);
-      case 4: return launch_v<bf16_t, 4>(k, s);
-      case 2: return launch_v<bf16_t, 2>(k, s);
-      default: return launch_v<bf16_t, 1>(k, s);
+      case 8: return launch_v<bf16_t, 8>(k, pf, s);
+      case 4: return launch_v<bf16_t, 4>(k, pf, s);
+      case 2: return launch_v<bf16_t, 2>(k, pf, s);
+      default: return launch_v<bf16_t, 1>(k, pf, s);
     }
   }
   switch (V) {
-    case 4: return launch_v<float, 4>(k, s);
-    case 2: return launch_v<float, 2>(k, s);
-    default: return launch_v<float, 1>(k, s);
+    case 4: return launch_v<float, 4>(k, pf, s);
+    case 2: return launch_v<float, 2>(k, pf, s);
+    default: return launch_v<float, 1>(k, pf, s);
   }
 }
 
@@ -288,7 +300,7 @@ extern "C" int gcn_spmm(const gcn_csr_t* A, const void* X, int64_t ldx, int d, i
   if (epilogue == GCN_EPI_MASK && (!Zprev || ldz < d)) return fail(GCN_EINVAL, "gcn_spmm: mask epilogue needs Zprev with ldz >= d");
   gcn_csr* Am = const_cast<gcn_csr*>(A);
   GCN_TRY(ensure_workspace(Am, spmm_ws_bytes(&A->sched, d)));
-  SpmmArgs a{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nr, X, ldx, Y, ldy, nullptr, 0,
+  SpmmArgs a{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, X, ldx, Y, ldy, nullptr, 0,
              d, dtype, epilogue, bias, Zprev, ldz};
   return spmm_launch(a, Am->ws, (hipStream_t)stream);
 }
@@ -303,7 +315,7 @@ extern "C" int gcn_spmm_t(const gcn_csr_t* A, const void* X, int64_t ldx, int d,
   if (epilogue == GCN_EPI_MASK && (!Zprev || ldz < d)) return fail(GCN_EINVAL, "gcn_spmm_t: mask epilogue needs Zprev with ldz >= d");
   gcn_csr* Am = const_cast<gcn_csr*>(A);
   GCN_TRY(ensure_workspace(Am, spmm_ws_bytes(&A->sched_t, d)));
-  SpmmArgs a{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, X, ldx, Y, ldy, nullptr, 0,
+  SpmmArgs a{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, X, ldx, Y, ldy, nullptr, 0,
              d, dtype, epilogue, nullptr, Zprev, ldz};
   return spmm_launch(a, Am->ws, (hipStream_t)stream);
 }
