@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-frac", type=float, default=None)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain row copy of known size (for scaling hardware byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the row block of one processor); "
@@ -151,6 +153,16 @@ def main():
     loss = float(ep.loss.item())
     log(f"{ms_per_step:.3f} ms/epoch, loss={loss:.5f}")
 
+    if args.calibrate_copy:
+        # identity gather = plain copy: reads 2^19 x 128 fp32 (256 MiB) + 2 MiB of indices, writes 256 MiB
+        rows = 1 << 19
+        T = torch.ones(rows, 128, device=dev)
+        R = torch.empty_like(T)
+        idx = torch.arange(rows, dtype=torch.int32, device=dev)
+        gcn.gcn_halo_gather(T, idx, R)
+        torch.cuda.synchronize()
+        del T, R, idx
+
     recs, dropped = gcn.gcn_profile_records()
     groups = {}
     for r in recs:
@@ -192,7 +204,7 @@ def main():
     if not args.no_cpu_baseline:
         frac = args.cpu_sample_frac
         if frac is None:
-            frac = min(1.0, 4.0e6 / max(A.nnz, 1))          # about 4 M stored entries of oracle work
+            frac = min(1.0, 2.0e7 / max(A.nnz, 1))          # about 20 M stored entries of oracle work
         out["cpu_baseline"] = cpu_baseline(w, frac)
     A.free()
     print(json.dumps(out), flush=True)
