@@ -61,6 +61,9 @@ struct Schedule {
   int64_t* hub_chunk_ptr = nullptr;  // [n_hub_rows+1] first chunk of each hub row
   int32_t* chunk_hub = nullptr;      // [n_chunks] index into hub_rows of each chunk
   int64_t n_chunks = 0;
+  // host copy: rows of length class c (lengths in [2^(31-c), 2^(32-c)); class 32 = empty rows) are
+  // wave_rows[class_begin[c] .. class_begin[c+1]); classes are stored longest first.
+  int64_t class_begin[34] = {0};
 };
 
 }  // namespace gcn

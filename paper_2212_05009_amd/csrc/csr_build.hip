@@ -255,7 +255,14 @@ int build_schedule(const int64_t* ptr, int64_t n, hipStream_t s, Schedule* out) 
   GCN_TRY(hub_rows.alloc(sizeof(int32_t) * (size_t)(n_hub > 0 ? n_hub : 1)));
   GCN_TRY(hub_chunk_ptr.alloc(sizeof(int64_t) * (size_t)(n_hub + 1)));
   GCN_TRY(chunk_hub.alloc(sizeof(int32_t) * (size_t)(n_chunks > 0 ? n_chunks : 1)));
-  if (n_wave > 0) k_take_low32<<<grid_for(n_wave), kThreads, 0, s>>>(sorted, n_wave, wave_rows.as<int32_t>());
+  DevBuf class_begin;
+  GCN_TRY(class_begin.alloc(sizeof(int64_t) * 34));
+  GCN_HIP(hipMemsetAsync(class_begin.p, 0, sizeof(int64_t) * 34, s));
+  if (n_wave > 0) {
+    k_take_low32<<<grid_for(n_wave), kThreads, 0, s>>>(sorted, n_wave, wave_rows.as<int32_t>());
+    k_boundaries<<<grid_for(n_wave), kThreads, 0, s>>>(sorted, n_wave, 32, 33, class_begin.as<int64_t>());
+  }
+  GCN_HIP(hipMemcpyAsync(out->class_begin, class_begin.p, sizeof(int64_t) * 34, hipMemcpyDeviceToHost, s));
   GCN_HIP(hipMemsetAsync(hub_chunk_ptr.p, 0, sizeof(int64_t) * (size_t)(n_hub + 1), s));
   if (n_hub > 0)
     k_hub_lists<<<grid_for(n), kThreads, 0, s>>>(hub_flag.as<uint32_t>(), hub_pos.as<int64_t>(),

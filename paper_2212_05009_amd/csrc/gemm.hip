@@ -137,8 +137,7 @@ __global__ __launch_bounds__(256) void k_gemm_nn(NnArgs a) {
     if (kt + 1 < nk) fetch((kt + 1) * BK);
     const float* as = &As[buf][(wm * TM * 32 + (lane & 31)) * LDA_S + (lane >> 5)];
     const float* bs = &Bs[buf][(lane >> 5) * LDB_S + wn * TN * 32 + (lane & 31)];
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 2) {
+    auto mma = [&](int kk) {
       float av[TM], bv[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) av[i] = as[i * 32 * LDA_S + kk];
@@ -149,6 +148,13 @@ __global__ __launch_bounds__(256) void k_gemm_nn(NnArgs a) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+    };
+    const int kleft = a.K - kt * BK;
+    if (kleft >= BK) {
+#pragma unroll
+      for (int kk = 0; kk < BK; kk += 2) mma(kk);
+    } else {                                               // the zero padding beyond K is skipped
+      for (int kk = 0; kk < kleft; kk += 2) mma(kk);
     }
     if (kt + 1 < nk) stage(buf ^ 1);
     __syncthreads();
@@ -166,6 +172,14 @@ __global__ __launch_bounds__(256) void k_gemm_nn(NnArgs a) {
       const int n = n0 + (wn * TN + j) * 32 + (lane & 31);
       if (n >= a.N) continue;
       const float bias = a.bias ? a.bias[n] : 0.f;
+      // all mask values first, then all stores: the loads are in flight together
+      float keep[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+        keep[r] = 1.f;
+        if (Mk && m < a.mask_rows && m < a.M) keep[r] = ld<T>(Mk + m * a.ldmask + n);
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
@@ -173,7 +187,7 @@ __global__ __launch_bounds__(256) void k_gemm_nn(NnArgs a) {
         float v = acc[i][j][r] + bias;
         if (C2) st<T>(C2 + m * a.ldc2 + n, v);
         if (a.relu) v = v > 0.f ? v : 0.f;
-        if (Mk && m < a.mask_rows) v = ld<T>(Mk + m * a.ldmask + n) > 0.f ? v : 0.f;
+        v = keep[r] > 0.f ? v : 0.f;
         st<T>(C + m * a.ldc + n, v);
       }
     }
@@ -219,57 +233,67 @@ int gemm_nn(const void* A, int64_t lda, const float* B, int64_t ldb, void* C, in
 // TN: C = A^T B over a long reduction.  Block (split, tile_m, tile_n) reduces rows
 // [split*rows_per_split, ...) into a 128 x 128 partial tile.
 // ------------------------------------------------------------------------------------------
-constexpr int TN_BN = 128;
 struct TnArgs {
   const void* A; int64_t lda; const void* B; int64_t ldb;
   int64_t Kd; int M; int N; int vecA; int vecB; int64_t rows_per_split; int nsplit;
   float* partial;   // [nsplit][M*N]
 };
 
-template <typename T>
+// WAVES_M x WAVES_N wavefronts, each TM x TN accumulator tiles of 32 x 32, on a 128 x BN output tile
+template <typename T, int BN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
-  constexpr int LDS_S = BM + BPAD;
-  __shared__ float As[2][BK * LDS_S];
-  __shared__ float Bs[2][BK * LDS_S];
+  static_assert(WAVES_M * WAVES_N == 4, "4 wavefronts per block");
+  constexpr int TM = BM / WAVES_M / 32, TN = BN / WAVES_N / 32;
+  constexpr int LDA_S = BM + BPAD, LDB_S = BN + BPAD;
+  __shared__ float As[2][BK * LDA_S];
+  __shared__ float Bs[2][BK * LDB_S];
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-  const int wm = w >> 1, wn = w & 1;            // 2 x 2 wavefronts, 64 x 64 each
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.z * TN_BN;
+  const int wm = w / WAVES_N, wn = w % WAVES_N;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.z * BN;
   const int64_t k_lo = (int64_t)blockIdx.x * a.rows_per_split;
   const int64_t k_hi = k_lo + a.rows_per_split < a.Kd ? k_lo + a.rows_per_split : a.Kd;
   const T* __restrict__ A = reinterpret_cast<const T*>(a.A);
   const T* __restrict__ B = reinterpret_cast<const T*>(a.B);
 
-  floatx16 acc[2][2];
+  floatx16 acc[TM][TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  constexpr int IT = BK * BM / 4 / 256;   // 4 quads per thread per operand
-  float ra[IT][4], rb[IT][4];
+  constexpr int A_IT = BK * BM / 4 / 256;
+  constexpr int B_IT = (BK * BN / 4 + 255) / 256;
+  float ra[A_IT][4], rb[B_IT][4];
   auto fetch = [&](int64_t k0) {
 #pragma unroll
-    for (int it = 0; it < IT; ++it) {
+    for (int it = 0; it < A_IT; ++it) {
       const int q = it * 256 + t;
       const int k = q / (BM / 4), cq = (q % (BM / 4)) * 4;
-      if (k0 + k < k_hi) {
-        load4<T>(A + (k0 + k) * a.lda, m0 + cq, a.M, a.vecA, ra[it]);
-        load4<T>(B + (k0 + k) * a.ldb, n0 + cq, a.N, a.vecB, rb[it]);
-      } else {
-        ra[it][0] = ra[it][1] = ra[it][2] = ra[it][3] = 0.f;
-        rb[it][0] = rb[it][1] = rb[it][2] = rb[it][3] = 0.f;
-      }
+      if (k0 + k < k_hi) load4<T>(A + (k0 + k) * a.lda, m0 + cq, a.M, a.vecA, ra[it]);
+      else { ra[it][0] = ra[it][1] = ra[it][2] = ra[it][3] = 0.f; }
+    }
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int q = it * 256 + t;
+      const int k = q / (BN / 4), cq = (q % (BN / 4)) * 4;
+      if (k < BK && k0 + k < k_hi) load4<T>(B + (k0 + k) * a.ldb, n0 + cq, a.N, a.vecB, rb[it]);
+      else { rb[it][0] = rb[it][1] = rb[it][2] = rb[it][3] = 0.f; }
     }
   };
   auto stage = [&](int buf) {
 #pragma unroll
-    for (int it = 0; it < IT; ++it) {
+    for (int it = 0; it < A_IT; ++it) {
       const int q = it * 256 + t;
       const int k = q / (BM / 4), cq = (q % (BM / 4)) * 4;
-      *reinterpret_cast<float4*>(&As[buf][k * LDS_S + cq]) = make_float4(ra[it][0], ra[it][1], ra[it][2], ra[it][3]);
-      *reinterpret_cast<float4*>(&Bs[buf][k * LDS_S + cq]) = make_float4(rb[it][0], rb[it][1], rb[it][2], rb[it][3]);
+      *reinterpret_cast<float4*>(&As[buf][k * LDA_S + cq]) = make_float4(ra[it][0], ra[it][1], ra[it][2], ra[it][3]);
+    }
+#pragma unroll
+    for (int it = 0; it < B_IT; ++it) {
+      const int q = it * 256 + t;
+      const int k = q / (BN / 4), cq = (q % (BN / 4)) * 4;
+      if (k < BK) *reinterpret_cast<float4*>(&Bs[buf][k * LDB_S + cq]) = make_float4(rb[it][0], rb[it][1], rb[it][2], rb[it][3]);
     }
   };
 
@@ -282,17 +306,19 @@ __global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
   for (int64_t kt = 0; kt < nk; ++kt) {
     const int buf = (int)(kt & 1);
     if (kt + 1 < nk) fetch(k_lo + (kt + 1) * BK);
-    const float* as = &As[buf][(lane >> 5) * LDS_S + wm * 64 + (lane & 31)];
-    const float* bs = &Bs[buf][(lane >> 5) * LDS_S + wn * 64 + (lane & 31)];
+    const float* as = &As[buf][(lane >> 5) * LDA_S + wm * TM * 32 + (lane & 31)];
+    const float* bs = &Bs[buf][(lane >> 5) * LDB_S + wn * TN * 32 + (lane & 31)];
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
-      float av[2], bv[2];
-      av[0] = as[kk * LDS_S]; av[1] = as[kk * LDS_S + 32];
-      bv[0] = bs[kk * LDS_S]; bv[1] = bs[kk * LDS_S + 32];
+      float av[TM], bv[TN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < TM; ++i) av[i] = as[kk * LDA_S + i * 32];
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TN; ++j) bv[j] = bs[kk * LDB_S + j * 32];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) stage(buf ^ 1);
@@ -300,31 +326,44 @@ __global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
   }
   float* __restrict__ P = a.partial + (int64_t)blockIdx.x * a.M * a.N;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int n = n0 + wn * 64 + j * 32 + (lane & 31);
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + (wn * TN + j) * 32 + (lane & 31);
       if (n >= a.N) continue;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * 64 + i * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+        const int m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
         if (m < a.M) P[(int64_t)m * a.N + n] = acc[i][j][r];
       }
     }
 }
 
-// C[e] = sum over splits of partial[s][e], accumulated in fp64 in split order
-__global__ void k_tn_reduce(const float* __restrict__ partial, int nsplit, int64_t mn, int N,
-                            float* __restrict__ C, int64_t ldc) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= mn) return;
+// C[e] = sum over splits of partial[s][e] in fp64 with a fixed association: a block takes 16
+// consecutive elements; thread (r, el) adds the splits r, r+16, ... of element el, then the 16
+// partial sums of an element are added in order of r.
+__global__ __launch_bounds__(256) void k_tn_reduce(const float* __restrict__ partial, int nsplit, int64_t mn, int N,
+                                                   float* __restrict__ C, int64_t ldc) {
+  __shared__ double red[16][17];
+  const int el = threadIdx.x & 15, r = threadIdx.x >> 4;
+  const int64_t e = (int64_t)blockIdx.x * 16 + el;
   double s = 0.0;
-  for (int p = 0; p < nsplit; ++p) s += (double)partial[(int64_t)p * mn + e];
-  C[(e / N) * ldc + (e % N)] = (float)s;
+  if (e < mn)
+    for (int p = r; p < nsplit; p += 16) s += (double)partial[(int64_t)p * mn + e];
+  red[r][el] = s;
+  __syncthreads();
+  if (r == 0 && e < mn) {
+    double t = 0.0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) t += red[q][el];
+    C[(e / N) * ldc + (e % N)] = (float)t;
+  }
 }
 
+static int tn_bn(int N) { return N <= 32 ? 32 : (N <= 64 ? 64 : 128); }
+
 static int tn_splits(int64_t Kd, int M, int N) {
-  const int64_t tiles = ceil_div(M, BM) * ceil_div(N, TN_BN);
+  const int64_t tiles = ceil_div(M, BM) * ceil_div(N, tn_bn(N));
   int64_t want = ceil_div(512, tiles);                 // about two blocks per compute unit
   int64_t max_by_k = ceil_div(Kd, 256);                // at least 256 rows per split
   int64_t ns = want < max_by_k ? want : max_by_k;
@@ -342,18 +381,26 @@ int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, in
   if (dtype == GCN_BF16) { if (a.vecA == 2) a.vecA = 1; if (a.vecB == 2) a.vecB = 1; }
   a.nsplit = tn_splits(Kd, M, N);
   a.rows_per_split = round_up(ceil_div(Kd > 0 ? Kd : 1, a.nsplit), BK);
-  dim3 grid((unsigned)a.nsplit, (unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, TN_BN));
+  const int bn = tn_bn(N);
+  dim3 grid((unsigned)a.nsplit, (unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, bn));
   const int64_t mn = (int64_t)M * N;
   {
     const double nb = (double)es * (double)Kd * (M + N) + 4.0 * (double)mn;
     ProfScope ps(GCN_K_GEMM_TN, s, N, dtype, M, Kd, nb, nb, 2.0 * (double)Kd * M * N);
-    if (dtype == GCN_BF16) k_gemm_tn<bf16_t><<<grid, 256, 0, s>>>(a);
-    else k_gemm_tn<float><<<grid, 256, 0, s>>>(a);
+    if (dtype == GCN_BF16) {
+      if (bn == 32) k_gemm_tn<bf16_t, 32, 4, 1><<<grid, 256, 0, s>>>(a);
+      else if (bn == 64) k_gemm_tn<bf16_t, 64, 4, 1><<<grid, 256, 0, s>>>(a);
+      else k_gemm_tn<bf16_t, 128, 2, 2><<<grid, 256, 0, s>>>(a);
+    } else {
+      if (bn == 32) k_gemm_tn<float, 32, 4, 1><<<grid, 256, 0, s>>>(a);
+      else if (bn == 64) k_gemm_tn<float, 64, 4, 1><<<grid, 256, 0, s>>>(a);
+      else k_gemm_tn<float, 128, 2, 2><<<grid, 256, 0, s>>>(a);
+    }
   }
   {
     const double nb = 4.0 * (double)mn * (a.nsplit + 1);
     ProfScope ps(GCN_K_GEMM_TN_SUM, s, N, GCN_F32, M, a.nsplit, nb, nb, (double)mn * a.nsplit);
-    k_tn_reduce<<<(unsigned)ceil_div(mn, 256), 256, 0, s>>>(a.partial, a.nsplit, mn, N, C, ldc);
+    k_tn_reduce<<<(unsigned)ceil_div(mn, 16), 256, 0, s>>>(a.partial, a.nsplit, mn, N, C, ldc);
   }
   GCN_CHECK_LAUNCH();
   return GCN_OK;

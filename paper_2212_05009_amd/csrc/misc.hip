@@ -72,7 +72,7 @@ static int gather_v(const char* table, int64_t ldb, int64_t nt, int n_vec, const
 // last layer): one group of LPR lanes per row.  The loss terms are added in fp64: per thread,
 // then per block in a fixed tree, then over the blocks in block order.
 // ------------------------------------------------------------------------------------------
-constexpr int kLossBlocks = 1024;
+constexpr int kLossBlocks = 8192;
 __device__ double g_loss_partial[kLossBlocks];
 
 template <typename T> __device__ __forceinline__ float ldf(const T* p) {
@@ -129,12 +129,18 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, i
   if (threadIdx.x == 0) g_loss_partial[blockIdx.x] = red[0];
 }
 
-__global__ void k_loss_finish(int nblocks, float scale, float* __restrict__ loss) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    double s = 0.0;
-    for (int b = 0; b < nblocks; ++b) s += g_loss_partial[b];
-    *loss = (float)((double)scale * s);
+// one block: thread t adds the partials t, t+256, ... in order, then a fixed tree over the threads
+__global__ __launch_bounds__(256) void k_loss_finish(int nblocks, float scale, float* __restrict__ loss) {
+  __shared__ double red[256];
+  double s = 0.0;
+  for (int b = threadIdx.x; b < nblocks; b += 256) s += g_loss_partial[b];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
   }
+  if (threadIdx.x == 0) *loss = (float)((double)scale * red[0]);
 }
 
 template <typename T>
@@ -153,7 +159,7 @@ static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* 
     case 32: k_softmax_xent<T, 32><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
     default: k_softmax_xent<T, 64><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
   }
-  k_loss_finish<<<1, 64, 0, s>>>(nb, scale, loss);
+  k_loss_finish<<<1, 256, 0, s>>>(nb, scale, loss);
   GCN_CHECK_LAUNCH();
   return GCN_OK;
 }
