@@ -39,7 +39,10 @@ class Epoch:
         assert A.nh == 0, "whole-graph epoch"
         # activations H[k] (input of layer k), pre-activations Z[k], gradients G[k] w.r.t. Z[k]
         self.H = [X] + [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L - 1)]
-        self.Z = [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L)]
+        # pre-activations are kept for the last layer only: a hidden layer's ReLU mask [Z > 0] is read
+        # off its output H = max(Z, 0), which is positive exactly where Z is
+        self.Z = [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) if k == self.L - 1 else None
+                  for k in range(self.L)]
         self.G = [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L)]
         # A^ H is kept for the weight gradient where the forward pass computes it anyway
         self.AH = [torch.empty(nr, dims[k], dtype=fdt, device=dev) if dims[k] <= dims[k + 1] else None
@@ -53,11 +56,11 @@ class Epoch:
             last = k == L - 1
             out = self.Z[k] if last else self.H[k + 1]
             g.gcn_layer_fwd(A, self.H[k], self.Ws[k], out, act=g.ACT_NONE if last else g.ACT_RELU,
-                            Z=None if last else self.Z[k], AH_save=self.AH[k])
+                            AH_save=self.AH[k])
         g.gcn_softmax_xent(self.Z[L - 1], self.y, 1.0 / A.nr, self.loss, self.G[L - 1])
         for k in range(L - 1, -1, -1):
             g.gcn_layer_bwd(A, self.H[k], self.Ws[k], self.G[k], self.dW[k],
-                            dH=self.G[k - 1] if k > 0 else None, Zprev=self.Z[k - 1] if k > 0 else None,
+                            dH=self.G[k - 1] if k > 0 else None, Zprev=self.H[k] if k > 0 else None,
                             AH_saved=self.AH[k])
 
 

@@ -30,7 +30,7 @@ template <typename T> __device__ __forceinline__ void st(T* p, float v) {
 }
 
 constexpr int BM = 128;    // output rows per block (NN) / A-columns per block (TN)
-constexpr int BK = 32;     // reduction step
+constexpr int BK = 16;     // reduction step
 constexpr int APAD = 1;    // As row-major [BM][BK + APAD]: bank-conflict-free MFMA operand reads
 constexpr int BPAD = 4;    // Bs [BK][BN + BPAD]
 
@@ -62,6 +62,19 @@ __device__ __forceinline__ void load4(const T* __restrict__ row, int64_t c, int6
   for (int i = 0; i < 4; ++i) o[i] = (c + i < limit) ? ld<T>(row + c + i) : 0.f;
 }
 
+// 4 consecutive elements from a 16-byte (fp32) / 8-byte (bf16) aligned address, no bounds checks
+template <typename T>
+__device__ __forceinline__ void load4_fast(const T* __restrict__ p, float (&o)[4]) {
+  if constexpr (sizeof(T) == 4) {
+    float4 v = *reinterpret_cast<const float4*>(p);
+    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+  } else {
+    uint2 v = *reinterpret_cast<const uint2*>(p);
+    o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+    o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+  }
+}
+
 struct NnArgs {
   const void* A; int64_t lda; const float* B; int64_t ldb; void* C; int64_t ldc;
   int64_t M; int N; int K; int vecA; int vecB;
@@ -70,7 +83,7 @@ struct NnArgs {
 
 // WAVES_M x WAVES_N wavefronts; each owns TM x TN accumulator tiles of 32 x 32
 template <typename T, int BN, int WAVES_M, int WAVES_N>
-__global__ __launch_bounds__(256) void k_gemm_nn(NnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_gemm_nn(NnArgs a) {
   static_assert(WAVES_M * WAVES_N == 4, "4 wavefronts per block");
   constexpr int TM = BM / WAVES_M / 32, TN = BN / WAVES_N / 32;
   constexpr int LDA_S = BK + APAD, LDB_S = BN + BPAD;
@@ -94,22 +107,43 @@ __global__ __launch_bounds__(256) void k_gemm_nn(NnArgs a) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   float ra[A_IT][4], rb[B_IT][4];
+  // interior tiles of aligned operands take plain 16-byte loads; edges go element by element
+  const bool a_in = a.vecA == 4 && m0 + BM <= a.M;
+  const bool b_in = a.vecB == 4 && n0 + BN <= a.N;
   auto fetch = [&](int k0) {
+    const bool k_in = k0 + BK <= a.K;
+    if (a_in && k_in) {
 #pragma unroll
-    for (int it = 0; it < A_IT; ++it) {
-      const int q = it * 256 + t;                 // group id: row = q / 8, k-quad = q % 8
-      const int64_t row = m0 + q / (BK / 4);
-      const int kq = (q % (BK / 4)) * 4;
-      if (row < a.M) load4<T>(A + row * a.lda, k0 + kq, a.K, a.vecA, ra[it]);
-      else { ra[it][0] = ra[it][1] = ra[it][2] = ra[it][3] = 0.f; }
+      for (int it = 0; it < A_IT; ++it) {
+        const int q = it * 256 + t;
+        load4_fast<T>(A + (m0 + q / (BK / 4)) * a.lda + k0 + (q % (BK / 4)) * 4, ra[it]);
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < A_IT; ++it) {
+        const int q = it * 256 + t;                 // group id: row = q / (BK/4), k-quad = q % (BK/4)
+        const int64_t row = m0 + q / (BK / 4);
+        const int kq = (q % (BK / 4)) * 4;
+        if (row < a.M) load4<T>(A + row * a.lda, k0 + kq, a.K, a.vecA, ra[it]);
+        else { ra[it][0] = ra[it][1] = ra[it][2] = ra[it][3] = 0.f; }
+      }
     }
+    if (b_in && k_in) {
 #pragma unroll
-    for (int it = 0; it < B_IT; ++it) {
-      const int q = it * 256 + t;                 // group id: k = q / (BN/4), n-quad = q % (BN/4)
-      const int k = q / (BN / 4);
-      const int nq = (q % (BN / 4)) * 4;
-      if (k < BK && k0 + k < a.K) load4<float>(a.B + (int64_t)(k0 + k) * a.ldb, n0 + nq, a.N, a.vecB, rb[it]);
-      else { rb[it][0] = rb[it][1] = rb[it][2] = rb[it][3] = 0.f; }
+      for (int it = 0; it < B_IT; ++it) {
+        const int q = it * 256 + t;
+        if (B_IT * 256 == BK * BN / 4 || q < BK * BN / 4)
+          load4_fast<float>(a.B + (int64_t)(k0 + q / (BN / 4)) * a.ldb + n0 + (q % (BN / 4)) * 4, rb[it]);
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < B_IT; ++it) {
+        const int q = it * 256 + t;                 // group id: k = q / (BN/4), n-quad = q % (BN/4)
+        const int k = q / (BN / 4);
+        const int nq = (q % (BN / 4)) * 4;
+        if (k < BK && k0 + k < a.K) load4<float>(a.B + (int64_t)(k0 + k) * a.ldb, n0 + nq, a.N, a.vecB, rb[it]);
+        else { rb[it][0] = rb[it][1] = rb[it][2] = rb[it][3] = 0.f; }
+      }
     }
   };
   auto stage = [&](int buf) {
@@ -137,7 +171,8 @@ __global__ __launch_bounds__(256) void k_gemm_nn(NnArgs a) {
     if (kt + 1 < nk) fetch((kt + 1) * BK);
     const float* as = &As[buf][(wm * TM * 32 + (lane & 31)) * LDA_S + (lane >> 5)];
     const float* bs = &Bs[buf][(lane >> 5) * LDB_S + wn * TN * 32 + (lane & 31)];
-    auto mma = [&](int kk) {
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {                   // the tile is zero beyond K
       float av[TM], bv[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) av[i] = as[i * 32 * LDA_S + kk];
@@ -148,13 +183,6 @@ __global__ __launch_bounds__(256) void k_gemm_nn(NnArgs a) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
-    };
-    const int kleft = a.K - kt * BK;
-    if (kleft >= BK) {
-#pragma unroll
-      for (int kk = 0; kk < BK; kk += 2) mma(kk);
-    } else {                                               // the zero padding beyond K is skipped
-      for (int kk = 0; kk < kleft; kk += 2) mma(kk);
     }
     if (kt + 1 < nk) stage(buf ^ 1);
     __syncthreads();
@@ -241,7 +269,7 @@ struct TnArgs {
 
 // WAVES_M x WAVES_N wavefronts, each TM x TN accumulator tiles of 32 x 32, on a 128 x BN output tile
 template <typename T, int BN, int WAVES_M, int WAVES_N>
-__global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) void k_gemm_tn(TnArgs a) {
   static_assert(WAVES_M * WAVES_N == 4, "4 wavefronts per block");
   constexpr int TM = BM / WAVES_M / 32, TN = BN / WAVES_N / 32;
   constexpr int LDA_S = BM + BPAD, LDB_S = BN + BPAD;
@@ -266,20 +294,40 @@ __global__ __launch_bounds__(256) void k_gemm_tn(TnArgs a) {
   constexpr int A_IT = BK * BM / 4 / 256;
   constexpr int B_IT = (BK * BN / 4 + 255) / 256;
   float ra[A_IT][4], rb[B_IT][4];
+  const bool a_in = a.vecA == 4 && m0 + BM <= a.M;
+  const bool b_in = a.vecB == 4 && n0 + BN <= a.N;
   auto fetch = [&](int64_t k0) {
+    const bool k_in = k0 + BK <= k_hi;
+    if (a_in && k_in) {
 #pragma unroll
-    for (int it = 0; it < A_IT; ++it) {
-      const int q = it * 256 + t;
-      const int k = q / (BM / 4), cq = (q % (BM / 4)) * 4;
-      if (k0 + k < k_hi) load4<T>(A + (k0 + k) * a.lda, m0 + cq, a.M, a.vecA, ra[it]);
-      else { ra[it][0] = ra[it][1] = ra[it][2] = ra[it][3] = 0.f; }
+      for (int it = 0; it < A_IT; ++it) {
+        const int q = it * 256 + t;
+        load4_fast<T>(A + (k0 + q / (BM / 4)) * a.lda + m0 + (q % (BM / 4)) * 4, ra[it]);
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < A_IT; ++it) {
+        const int q = it * 256 + t;
+        const int k = q / (BM / 4), cq = (q % (BM / 4)) * 4;
+        if (k0 + k < k_hi) load4<T>(A + (k0 + k) * a.lda, m0 + cq, a.M, a.vecA, ra[it]);
+        else { ra[it][0] = ra[it][1] = ra[it][2] = ra[it][3] = 0.f; }
+      }
     }
+    if (b_in && k_in) {
 #pragma unroll
-    for (int it = 0; it < B_IT; ++it) {
-      const int q = it * 256 + t;
-      const int k = q / (BN / 4), cq = (q % (BN / 4)) * 4;
-      if (k < BK && k0 + k < k_hi) load4<T>(B + (k0 + k) * a.ldb, n0 + cq, a.N, a.vecB, rb[it]);
-      else { rb[it][0] = rb[it][1] = rb[it][2] = rb[it][3] = 0.f; }
+      for (int it = 0; it < B_IT; ++it) {
+        const int q = it * 256 + t;
+        if (B_IT * 256 == BK * BN / 4 || q < BK * BN / 4)
+          load4_fast<T>(B + (k0 + q / (BN / 4)) * a.ldb + n0 + (q % (BN / 4)) * 4, rb[it]);
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < B_IT; ++it) {
+        const int q = it * 256 + t;
+        const int k = q / (BN / 4), cq = (q % (BN / 4)) * 4;
+        if (k < BK && k0 + k < k_hi) load4<T>(B + (k0 + k) * a.ldb, n0 + cq, a.N, a.vecB, rb[it]);
+        else { rb[it][0] = rb[it][1] = rb[it][2] = rb[it][3] = 0.f; }
+      }
     }
   };
   auto stage = [&](int buf) {
