@@ -28,22 +28,32 @@ def log(msg):
 
 
 class Epoch:
-    """Buffers and call sequence of one epoch; every step is a call into the C-ABI library."""
+    """Buffers and call sequence of one epoch; every step is a call into the C-ABI library.
 
-    def __init__(self, gcn, torch, A, X, Ws, y, bf16):
-        self.gcn, self.torch, self.A, self.X, self.Ws, self.y = gcn, torch, A, X, Ws, y
-        dev = X.device
+    Works on a row block: layer inputs hold the nr owned rows followed by the nh halo rows.  The halo rows
+    of every layer input are fetched through the halo index list from `table` (the stand-in for the rows
+    other processors would send) at the start of that layer, inside the timed epoch.
+    """
+
+    def __init__(self, gcn, torch, A, X_owned, Ws, y, bf16, table=None):
+        self.gcn, self.torch, self.A, self.Ws, self.y, self.table = gcn, torch, A, Ws, y, table
+        dev = X_owned.device
         fdt = torch.bfloat16 if bf16 else torch.float32
-        dims = [X.shape[1]] + [W.shape[1] for W in Ws]
-        self.dims, self.L, nr = dims, len(Ws), A.nr
-        assert A.nh == 0, "whole-graph epoch"
-        # activations H[k] (input of layer k), pre-activations Z[k], gradients G[k] w.r.t. Z[k]
-        self.H = [X] + [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L - 1)]
+        dims = [X_owned.shape[1]] + [W.shape[1] for W in Ws]
+        self.dims, self.L = dims, len(Ws)
+        nr, nc = A.nr, A.nc
+        assert (A.nh == 0) == (table is None), "a block with halo rows needs a table to fetch them from"
+        self.halo_gid = A.arrays()["halo_gid"] if A.nh else None
+        # H[k]: input of layer k, [nc, dims[k]]; the owned rows of H[k+1] are layer k's output
+        self.H = [torch.empty(nc, dims[k], dtype=fdt, device=dev) for k in range(self.L)]
+        self.H[0][:nr] = X_owned
         # pre-activations are kept for the last layer only: a hidden layer's ReLU mask [Z > 0] is read
         # off its output H = max(Z, 0), which is positive exactly where Z is
-        self.Z = [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) if k == self.L - 1 else None
-                  for k in range(self.L)]
-        self.G = [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L)]
+        self.Zlast = torch.empty(nr, dims[self.L], dtype=fdt, device=dev)
+        # D[k]: gradient w.r.t. the input rows of layer k+1 ([nc, dims[k+1]]: owned rows, then this block's
+        # contributions to halo rows); its owned rows are G[k], the gradient w.r.t. Z of layer k
+        self.D = [torch.empty(nc, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L - 1)]
+        self.G = [d[:nr] for d in self.D] + [torch.empty(nr, dims[self.L], dtype=fdt, device=dev)]
         # A^ H is kept for the weight gradient where the forward pass computes it anyway
         self.AH = [torch.empty(nr, dims[k], dtype=fdt, device=dev) if dims[k] <= dims[k + 1] else None
                    for k in range(self.L)]
@@ -51,48 +61,54 @@ class Epoch:
         self.loss = torch.zeros(1, device=dev)
 
     def run(self):
-        g, A, L = self.gcn, self.A, self.L
+        g, A, L, nr = self.gcn, self.A, self.L, self.A.nr
         for k in range(L):
             last = k == L - 1
-            out = self.Z[k] if last else self.H[k + 1]
+            if A.nh:
+                g.gcn_halo_gather(self.table, self.halo_gid, self.H[k][nr:])
+            out = self.Zlast if last else self.H[k + 1][:nr]
             g.gcn_layer_fwd(A, self.H[k], self.Ws[k], out, act=g.ACT_NONE if last else g.ACT_RELU,
                             AH_save=self.AH[k])
-        g.gcn_softmax_xent(self.Z[L - 1], self.y, 1.0 / A.nr, self.loss, self.G[L - 1])
+        g.gcn_softmax_xent(self.Zlast, self.y, 1.0 / nr, self.loss, self.G[L - 1])
         for k in range(L - 1, -1, -1):
             g.gcn_layer_bwd(A, self.H[k], self.Ws[k], self.G[k], self.dW[k],
-                            dH=self.G[k - 1] if k > 0 else None, Zprev=self.H[k] if k > 0 else None,
+                            dH=self.D[k - 1] if k > 0 else None, Zprev=self.H[k][:nr] if k > 0 else None,
                             AH_saved=self.AH[k])
 
 
 def cpu_baseline(w, frac):
-    """Time the oracle, as it stands, on one epoch over the row block [0, frac*n) of the same graph."""
+    """Time the oracle, as it stands, on one epoch over the first frac of the workload's owned rows."""
     import numpy as np
     import oracle
     from workloads import configs
     n, dims = w["n"], w["dims"]
-    hi = max(1, int(n * frac))
+    lo, hi_all = w.get("row_lo", 0), w.get("row_hi", n)
+    hi = lo + max(1, int((hi_all - lo) * frac))
     t0 = time.time()
-    whole = oracle.graph_build(w["src"], w["dst"], n)
-    blk = oracle.graph_build(w["src"], w["dst"], n, 0, hi, deg_global=whole.deg)
-    log(f"oracle graphs built in {time.time() - t0:.1f}s: block rows={blk.nr} halo={blk.nh} nnz={blk.nnz} of {whole.nnz}")
+    deg = w.get("deg_global")
+    if deg is None:
+        deg = oracle.graph_build(w["src"], w["dst"], n).deg
+    blk = oracle.graph_build(w["src"], w["dst"], n, lo, hi, deg_global=deg)
+    in_all = int(np.count_nonzero((w["src"] >= lo) & (w["src"] < hi_all)))
+    in_blk = int(np.count_nonzero((w["src"] >= lo) & (w["src"] < hi)))
+    log(f"oracle graph built in {time.time() - t0:.1f}s: rows={blk.nr} halo={blk.nh} nnz={blk.nnz}")
     L = len(dims) - 1
     Hs = [configs.features(blk.nc, dims[k], 900 + k) for k in range(L)]
-    Zp = [configs.features(blk.nr, dims[k], 950 + k) for k in range(L)]
     t0 = time.time()
     for k in range(L):
         oracle.layer_fwd(blk, Hs[k], w["W"][k], act="none" if k == L - 1 else "relu")
-    _, _, G = oracle.softmax_xent(configs.features(blk.nr, dims[L], 990), w["y"][:hi], 1.0 / hi)
+    _, _, G = oracle.softmax_xent(configs.features(blk.nr, dims[L], 990), w["y"][: blk.nr], 1.0 / blk.nr)
     G = G.astype(np.float32)
     for k in range(L - 1, -1, -1):
-        b = oracle.layer_bwd(blk, Hs[k], w["W"][k], G, Zprev=Zp[k] if k > 0 else None, want_dH=k > 0)
+        b = oracle.layer_bwd(blk, Hs[k], w["W"][k], G, Zprev=Hs[k][: blk.nr] if k > 0 else None, want_dH=k > 0)
         if k > 0:
             G = b["dH"][: blk.nr].astype(np.float32)
     sec = time.time() - t0
-    scale = whole.nnz / blk.nnz
+    scale = in_all / max(in_blk, 1)
     return {"value": sec * 1e3 * scale, "unit": "ms/epoch", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"one epoch (all layers forward, loss, backward; fp64, with bound sums) on the row block "
-                      f"[0,{hi}) of the same graph ({blk.nnz} of {whole.nnz} stored entries, halo {blk.nh} rows) took "
-                      f"{sec:.2f}s; value = that time x {scale:.2f} (ratio of stored entries)"}
+            "sample": f"one epoch (all layers forward, loss, backward; fp64, with bound sums; halo rows taken as "
+                      f"given) on rows [{lo},{hi}) of the same graph ({in_blk} of {in_all} raw edges, {blk.nnz} stored "
+                      f"entries, halo {blk.nh} rows) took {sec:.2f}s; value = that time x {scale:.2f} (ratio of raw edges)"}
 
 
 def main():
@@ -127,20 +143,34 @@ def main():
     log(f"workload {args.workload}: n={n} raw directed edges={w['src'].size} dims={dims} generated in {time.time() - t0:.1f}s")
 
     src, dst = torch.from_numpy(w["src"]).to(dev), torch.from_numpy(w["dst"]).to(dev)
+    block = "row_lo" in w
+    deg_global = torch.from_numpy(w["deg_global"]).to(dev) if block else None
     torch.cuda.synchronize()
     t0 = time.time()
-    A = gcn.gcn_csr_build(src, dst, n)
+    A = gcn.gcn_csr_build(src, dst, n, w.get("row_lo", 0), w.get("row_hi", n), deg_global=deg_global)
     torch.cuda.synchronize()
     build_ms = (time.time() - t0) * 1e3
-    del src, dst
-    log(f"csr+csc build: {build_ms:.1f} ms, nnz={A.nnz}")
+    del src, dst, deg_global
+    log(f"csr+csc build: {build_ms:.1f} ms, nr={A.nr} nh={A.nh} nnz={A.nnz}")
 
-    X = torch.from_numpy(w["X"]).to(dev)
-    if bf16:
-        X = X.to(torch.bfloat16)
+    table = None
+    if block:
+        from workloads import table as wtable
+        t0 = time.time()
+        table = torch.empty((n, dims[0]), dtype=torch.float32, pin_memory=True)      # host-resident feature table
+        wtable.fill_table_torch(table, w["table_seed"], dev)
+        X = table[w["row_lo"]: w["row_hi"]].to(dev)
+        log(f"host feature table {n} x {dims[0]} fp32 ({table.numel() * 4 / 2**30:.1f} GiB, pinned) filled in {time.time() - t0:.1f}s")
+        if bf16:
+            raise SystemExit("the block workload keeps its host table in fp32")
+    else:
+        X = torch.from_numpy(w["X"]).to(dev)
+        if bf16:
+            X = X.to(torch.bfloat16)
     Ws = [torch.from_numpy(m).to(dev) for m in w["W"]]
     y = torch.from_numpy(w["y"]).to(dev)
-    ep = Epoch(gcn, torch, A, X, Ws, y, bf16)
+    ep = Epoch(gcn, torch, A, X, Ws, y, bf16, table=table)
+    del X
 
     for _ in range(args.warmup):
         ep.run()
@@ -201,7 +231,8 @@ def main():
     out = {"metric": "GCN full-batch epoch ms (fwd+bwd) on 1 MI355X", "value": round(ms_per_step, 4), "unit": "ms/epoch",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
            "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-           "config": {"workload": args.workload, "n": n, "nnz": A.nnz, "dims": dims, "layers": len(dims) - 1},
+           "config": {"workload": args.workload, "n": n, "owned_rows": A.nr, "halo_rows": A.nh, "nnz": A.nnz, "dims": dims,
+                      "layers": len(dims) - 1},
            "epochs_per_s": round(1e3 / ms_per_step, 2), "loss": round(loss, 6), "csr_csc_build_ms": round(build_ms, 2),
            "roofline": roof, "kernels": kernels, "profile_records_dropped": dropped}
     if not args.no_cpu_baseline:

@@ -68,7 +68,7 @@ def test_fullsize_forward_rows(full):
     # layer 2 from the GPU's H1: Z2 = A^ (H1 W2) in the library, the same sum as (A^ H1) W2
     H1 = ep.H[1].cpu().numpy()
     AH, BAH = oracle.spmm(og.rowptr, og.col, og.val, H1, rows=rows)
-    check_bound(ep.Z[1][rows].cpu().numpy(), AH @ W2, BAH @ np.abs(W2), TOL_F32, "Z2 rows")
+    check_bound(ep.Zlast[rows].cpu().numpy(), AH @ W2, BAH @ np.abs(W2), TOL_F32, "Z2 rows")
     # the saved A^ X of layer 1
     check_bound(ep.AH[0][rows].cpu().numpy(), AX, BAX, TOL_F32, "saved A^X rows")
 
@@ -76,7 +76,7 @@ def test_fullsize_forward_rows(full):
 def test_fullsize_loss_and_output_gradient(full):
     w, ep = full["w"], full["ep"]
     n = w["n"]
-    Z2 = ep.Z[1].cpu().numpy()
+    Z2 = ep.Zlast.cpu().numpy()
     loss, labs, G = oracle.softmax_xent(Z2, w["y"], 1.0 / n)
     assert abs(float(ep.loss.item()) - loss) <= TOL_F32 * max(labs, np.abs(Z2).max() * 3)
     onehot = np.zeros_like(G); onehot[np.arange(n), w["y"]] = 1.0 / n

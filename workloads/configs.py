@@ -72,11 +72,37 @@ def sparse_large(n: int = 2_449_029, scale: int = 22, avg_degree: float = 50.5,
     return _pack(n, src, dst, dims, seed)
 
 
+def row_block(n_global: int = 1 << 25, n_rows: int = 1 << 22, n_halo: int = 6 << 20, avg_degree: float = 16.0,
+              dims=(128, 128, 32), seed: int = BASE_SEED + 5):
+    """Config 5: one processor's row block of a much larger power-law graph (owned rows + halo columns).
+
+    Extra keys: row_lo, row_hi, deg_global (int32 [n]: entries of each vertex's row of A + I; exact for the
+    owned rows, drawn from the same row-length law for the halo vertices, 1 elsewhere), table_seed (the
+    feature table is workloads.table: every row recomputable).  y has one label per owned row; no X.
+    """
+    row_lo = (n_global // 4 // 64) * 64
+    src, dst, halo_ids = graphs.row_block(n_global, row_lo, n_rows, n_halo, avg_degree, 0.5, seed)
+    # exact degrees of the owned rows: distinct non-diagonal columns, plus the diagonal of I
+    off = src != dst
+    key = np.unique(((src[off].astype(np.int64) - row_lo) << 32) | dst[off].astype(np.int64))
+    deg = np.ones(n_global, dtype=np.int32)
+    deg[row_lo: row_lo + n_rows] += np.bincount((key >> 32).astype(np.int64), minlength=n_rows).astype(np.int32)
+    u = prng.uniform01(seed, 11, 0, n_halo)
+    raw = np.minimum((1.0 - u) ** (-1.0 / 1.2), 1.0e5)
+    deg[halo_ids] = np.maximum(2, np.floor(raw * (avg_degree - 1.0) / raw.mean() + 1.5)).astype(np.int32)
+    w = {"n": int(n_global), "src": src, "dst": dst, "dims": list(dims), "seed": seed,
+         "row_lo": int(row_lo), "row_hi": int(row_lo + n_rows), "deg_global": deg, "table_seed": seed + 100}
+    w["W"] = [glorot(dims[k], dims[k + 1], seed, k) for k in range(len(dims) - 1)]
+    w["y"] = labels(n_rows, dims[-1], seed)
+    return w
+
+
 WORKLOADS = {
     "c1_er4096": tiny_er,
     "c2_rmat18": rmat_powerlaw,
     "c3_dense233k": dense_neighbourhood,
     "c4_sparse2m4": sparse_large,
+    "c5_block": row_block,
 }
 
 
