@@ -147,6 +147,14 @@ int gemm_nn(const void* A, int64_t lda, const float* B, int64_t ldb, void* C, in
 size_t gemm_tn_ws_bytes(int64_t Kdim, int M, int N);
 int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc,
             int64_t Kdim, int M, int N, int dtype, void* ws, hipStream_t s);
+// streaming variants (gemm_direct.hip): the long operand goes from global memory straight into the
+// MFMA operand registers; nn_direct needs W to fit in LDS (gemm_nn_direct_ok)
+bool gemm_nn_direct_ok(int N, int K);
+int gemm_nn_direct(const void* A, int64_t lda, const float* W, int64_t ldw, void* C, int64_t ldc, int64_t M, int N,
+                   int K, int dtype, const GemmEpilogue& epi, hipStream_t s);
+size_t gemm_tn_direct_ws_bytes(int64_t Kd, int M, int N);
+int gemm_tn_direct_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype,
+                            float* partial, int* nsplit_out, hipStream_t s);
 // Wt[N x K] = W[K x N]^T (f32, small)
 int transpose_f32(const float* W, int K, int N, float* Wt, hipStream_t s);
 // out[c] = sum_i G[i, c]  (deterministic), ws at least colsum_ws_bytes

@@ -8,6 +8,8 @@
 // A 256-thread block (4 wavefronts) owns a 128 x BN output tile and walks K in steps of 32,
 // staging both operand tiles in LDS (double buffered); each wavefront keeps a grid of 32x32
 // MFMA accumulator tiles in registers.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace gcn {
@@ -221,6 +223,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     }
 }
 
+static bool use_direct() {
+  const char* e = getenv("GCN_GEMM_DIRECT");      // override for experiments: 0 = LDS-tiled kernels only
+  return !(e && e[0] == '0');
+}
+
 static int pick_vec(const void* p, int64_t ld, int64_t extent, size_t es) {
   int v = 4;
   while (v > 1 && !((ld % v) == 0 && ((uintptr_t)p % (v * es)) == 0)) v >>= 1;
@@ -251,6 +258,11 @@ int gemm_nn(const void* A, int64_t lda, const float* B, int64_t ldb, void* C, in
             int K, int dtype, const GemmEpilogue& epi, hipStream_t s) {
   if (M == 0) return GCN_OK;
   const size_t es = dtype == GCN_BF16 ? 2 : 4;
+  if (use_direct() && gemm_nn_direct_ok(N, K)) {
+    const double nb = (double)es * (double)M * (K + N * (epi.C2 ? 2.0 : 1.0) + (epi.mask ? N : 0)) + 4.0 * (double)K * N;
+    ProfScope ps(GCN_K_GEMM_NN, s, N, dtype, M, K, nb, nb, 2.0 * (double)M * N * K);
+    return gemm_nn_direct(A, lda, B, ldb, C, ldc, M, N, K, dtype, epi, s);
+  }
   NnArgs a{A, lda, B, ldb, C, ldc, M, N, K, pick_vec(A, lda, K, es), pick_vec(B, ldb, N, 4),
            epi.bias, epi.relu, epi.mask, epi.ldmask, epi.mask_rows, epi.C2, epi.ldc2};
   if (dtype == GCN_BF16 && a.vecA == 2) a.vecA = 1;
@@ -419,20 +431,28 @@ static int tn_splits(int64_t Kd, int M, int N) {
 }
 
 size_t gemm_tn_ws_bytes(int64_t Kd, int M, int N) {
-  return sizeof(float) * (size_t)tn_splits(Kd, M, N) * (size_t)M * (size_t)N;
+  const size_t tiled = sizeof(float) * (size_t)tn_splits(Kd, M, N) * (size_t)M * (size_t)N;
+  const size_t direct = gemm_tn_direct_ws_bytes(Kd, M, N);
+  return tiled > direct ? tiled : direct;
 }
 
 int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc, int64_t Kd, int M,
             int N, int dtype, void* ws, hipStream_t s) {
   const size_t es = dtype == GCN_BF16 ? 2 : 4;
-  TnArgs a{A, lda, B, ldb, Kd, M, N, pick_vec(A, lda, M, es), pick_vec(B, ldb, N, es), 0, 0, (float*)ws};
-  if (dtype == GCN_BF16) { if (a.vecA == 2) a.vecA = 1; if (a.vecB == 2) a.vecB = 1; }
-  a.nsplit = tn_splits(Kd, M, N);
-  a.rows_per_split = round_up(ceil_div(Kd > 0 ? Kd : 1, a.nsplit), BK);
-  const int bn = tn_bn(N);
-  dim3 grid((unsigned)a.nsplit, (unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, bn));
   const int64_t mn = (int64_t)M * N;
-  {
+  int nsplit = 0;
+  if (use_direct()) {
+    const double nb = (double)es * (double)Kd * (M + N) + 4.0 * (double)mn;
+    ProfScope ps(GCN_K_GEMM_TN, s, N, dtype, M, Kd, nb, nb, 2.0 * (double)Kd * M * N);
+    GCN_TRY(gemm_tn_direct_partials(A, lda, B, ldb, Kd, M, N, dtype, (float*)ws, &nsplit, s));
+  } else {
+    TnArgs a{A, lda, B, ldb, Kd, M, N, pick_vec(A, lda, M, es), pick_vec(B, ldb, N, es), 0, 0, (float*)ws};
+    if (dtype == GCN_BF16) { if (a.vecA == 2) a.vecA = 1; if (a.vecB == 2) a.vecB = 1; }
+    a.nsplit = tn_splits(Kd, M, N);
+    a.rows_per_split = round_up(ceil_div(Kd > 0 ? Kd : 1, a.nsplit), BK);
+    nsplit = a.nsplit;
+    const int bn = tn_bn(N);
+    dim3 grid((unsigned)a.nsplit, (unsigned)ceil_div(M, BM), (unsigned)ceil_div(N, bn));
     const double nb = (double)es * (double)Kd * (M + N) + 4.0 * (double)mn;
     ProfScope ps(GCN_K_GEMM_TN, s, N, dtype, M, Kd, nb, nb, 2.0 * (double)Kd * M * N);
     if (dtype == GCN_BF16) {
@@ -446,9 +466,9 @@ int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, in
     }
   }
   {
-    const double nb = 4.0 * (double)mn * (a.nsplit + 1);
-    ProfScope ps(GCN_K_GEMM_TN_SUM, s, N, GCN_F32, M, a.nsplit, nb, nb, (double)mn * a.nsplit);
-    k_tn_reduce<<<(unsigned)ceil_div(mn, 16), 256, 0, s>>>(a.partial, a.nsplit, mn, N, C, ldc);
+    const double nb = 4.0 * (double)mn * (nsplit + 1);
+    ProfScope ps(GCN_K_GEMM_TN_SUM, s, N, GCN_F32, M, nsplit, nb, nb, (double)mn * nsplit);
+    k_tn_reduce<<<(unsigned)ceil_div(mn, 16), 256, 0, s>>>((const float*)ws, nsplit, mn, N, C, ldc);
   }
   GCN_CHECK_LAUNCH();
   return GCN_OK;

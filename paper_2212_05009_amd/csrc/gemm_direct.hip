@@ -1,0 +1,401 @@
+// Streaming forms of the two tall-and-skinny dense products of a GCN layer (Sec. 3.1: the product
+// with W^k after the sparse aggregation, and the weight gradient), for gfx950.  The long operand
+// (one row per vertex) goes from global memory straight into the MFMA operand registers: no LDS
+// staging and no barrier in the main loop, so a wavefront keeps many independent loads in flight,
+// which is what a product bound by HBM bandwidth needs.
+//
+//   nn_direct : C[M x N] = A[M x K] W[K x N], W small enough to sit in LDS for the whole kernel.
+//               MFMA 16x16x4: lane (c = l%16, q = l/16) loads A[row c][k0 + 4q .. k0 + 4q + 3] with one
+//               16-byte load and feeds element i of it to the i-th of four MFMAs, whose W operand is
+//               W[k0 + 4q + i][col c]: every k of the 16-wide step is used exactly once, only in a
+//               permuted order, which a sum does not care about.
+//   tn_direct : C[M x N] = A[Kd x M]^T B[Kd x N], Kd = number of vertices.  MFMA 32x32x2: lane
+//               (c = l%32, h = l/32) loads A[k + h][m0 + c] and B[k + h][n0 + c]: 128-byte coalesced
+//               rows.  The four wavefronts of a block take interleaved row chunks of one output tile,
+//               add their tiles through LDS and write one partial tile per block.
+#include "common.h"
+
+namespace gcn {
+
+typedef uint16_t bf16_t;
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+template <typename T> __device__ __forceinline__ float ldg(const T* p) {
+  if constexpr (sizeof(T) == 4) return (float)*p; else return __uint_as_float((uint32_t)(*p) << 16);
+}
+template <typename T> __device__ __forceinline__ void stg(T* p, float f) {
+  if constexpr (sizeof(T) == 4) { *p = f; }
+  else {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) { *p = (T)((u >> 16) | 0x40u); return; }
+    u += 0x7fffu + ((u >> 16) & 1u);
+    *p = (T)(u >> 16);
+  }
+}
+
+// 4 consecutive elements starting at column k (multiple of 4) of a row, zero beyond `limit`
+template <typename T>
+__device__ __forceinline__ void load_quad(const T* __restrict__ row, int k, int limit, bool vec_ok, float (&o)[4]) {
+  if (vec_ok && k + 3 < limit) {
+    if constexpr (sizeof(T) == 4) {
+      float4 v = *reinterpret_cast<const float4*>(row + k);
+      o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    } else {
+      uint2 v = *reinterpret_cast<const uint2*>(row + k);
+      o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+      o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+    }
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) o[i] = (k + i < limit) ? ldg<T>(row + k + i) : 0.f;
+}
+
+// 4 consecutive elements starting at column n (multiple of 4) of a row, none beyond `limit`
+template <typename T>
+__device__ __forceinline__ void store_quad(T* __restrict__ row, int n, int limit, bool vec_ok, const float (&v)[4]) {
+  if (vec_ok && n + 3 < limit) {
+    if constexpr (sizeof(T) == 4) {
+      *reinterpret_cast<float4*>(row + n) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+      bf16_t h[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) stg<T>(&h[i], v[i]);
+      uint2 pk;
+      pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+      pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+      *reinterpret_cast<uint2*>(row + n) = pk;
+    }
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    if (n + i < limit) stg<T>(row + n + i, v[i]);
+}
+
+// ------------------------------------------------------------------------------------------
+struct NnDirectArgs {
+  const void* A; int64_t lda; const float* W; int64_t ldw; void* C; int64_t ldc;
+  int64_t M; int N; int K; int vecA; int vecC; int vecC2; int vecM;
+  const float* bias; int relu; const void* mask; int64_t ldmask; int64_t mask_rows; void* C2; int64_t ldc2;
+};
+
+constexpr int kNnThreads = 512;
+constexpr int kNnKU = 8;          // 16-wide k steps whose loads are issued together
+
+template <typename T, int NT>
+__global__ __launch_bounds__(kNnThreads) void k_gemm_nn_direct(NnDirectArgs a) {
+  extern __shared__ float Ws[];                      // [Kp][LDW], zero beyond K and N
+  constexpr int LDW = NT * 16 + 4;                    // 4 k-rows apart land 16 banks apart
+  const int Kp = (a.K + 15) & ~15;
+  for (int e = threadIdx.x; e < Kp * NT * 16; e += kNnThreads) {
+    const int k = e / (NT * 16), n = e % (NT * 16);
+    Ws[k * LDW + n] = (k < a.K && n < a.N) ? a.W[(int64_t)k * a.ldw + n] : 0.f;
+  }
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = lane & 15, q = lane >> 4;
+  const T* __restrict__ A = reinterpret_cast<const T*>(a.A);
+  T* __restrict__ C = reinterpret_cast<T*>(a.C);
+  T* __restrict__ C2 = reinterpret_cast<T*>(a.C2);
+  const T* __restrict__ Mk = reinterpret_cast<const T*>(a.mask);
+  const bool vec_ok = a.vecA == 4;
+  const int64_t ntiles = (a.M + 15) / 16;
+  constexpr int WPB = kNnThreads / 64;
+
+  // Software pipeline over the tiles of this wavefront: the operand rows (first 128 k) and the mask
+  // values of the NEXT tile are requested before the current tile's MFMAs and stores, so that a
+  // wavefront always has a tile's worth of loads in flight.
+  constexpr int TC = NT < 8 ? NT : 8;                 // column tiles finished together (bounds registers)
+  constexpr bool kPrefetchMask = NT <= 8;
+  const int64_t stride = (int64_t)gridDim.x * WPB;
+  auto load_a = [&](int64_t tile, int k0, float (&av)[kNnKU][4]) {
+    const int64_t row = tile * 16 + c;
+    const T* __restrict__ arow = A + (row < a.M ? row : a.M - 1) * a.lda;
+#pragma unroll
+    for (int u = 0; u < kNnKU; ++u) {
+      if (k0 + 16 * u < Kp) load_quad<T>(arow, k0 + 16 * u + 4 * q, a.K, vec_ok, av[u]);
+      else { av[u][0] = av[u][1] = av[u][2] = av[u][3] = 0.f; }
+    }
+  };
+  auto load_m = [&](int64_t tile, int t0, float (&keep)[TC][4]) {
+    const int64_t m = tile * 16 + c;
+    const bool masked = Mk != nullptr && m < a.mask_rows && m < a.M;
+#pragma unroll
+    for (int t = 0; t < TC; ++t) {
+      keep[t][0] = keep[t][1] = keep[t][2] = keep[t][3] = 1.f;
+      if (masked && t0 + t < NT) load_quad<T>(Mk + m * a.ldmask, (t0 + t) * 16 + 4 * q, a.N, a.vecM == 4, keep[t]);
+    }
+  };
+
+  int64_t tile = (int64_t)blockIdx.x * WPB + w;
+  float a_nxt[kNnKU][4], m_nxt[TC][4];
+  if (tile < ntiles) {
+    load_a(tile, 0, a_nxt);
+    if (kPrefetchMask) load_m(tile, 0, m_nxt);
+  }
+  for (; tile < ntiles; tile += stride) {
+    float av[kNnKU][4], keep[TC][4];
+#pragma unroll
+    for (int u = 0; u < kNnKU; ++u)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) av[u][i] = a_nxt[u][i];
+    if (kPrefetchMask) {
+#pragma unroll
+      for (int t = 0; t < TC; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) keep[t][i] = m_nxt[t][i];
+    }
+    if (tile + stride < ntiles) {
+      load_a(tile + stride, 0, a_nxt);
+      if (kPrefetchMask) load_m(tile + stride, 0, m_nxt);
+    }
+
+    floatx4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int k0 = 0; k0 < Kp; k0 += 16 * kNnKU) {
+      if (k0 > 0) load_a(tile, k0, av);
+#pragma unroll
+      for (int u = 0; u < kNnKU; ++u) {
+        if (k0 + 16 * u < Kp) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float* wrow = Ws + (k0 + 16 * u + 4 * q + i) * LDW + c;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wrow[t * 16], av[u][i], acc[t], 0, 0, 0);
+          }
+        }
+      }
+    }
+
+    // W is the first MFMA operand, so the 16 x 16 result tile is transposed: register r of lane (c, q)
+    // holds output column 16t + 4q + r of row c.  A lane owns 4 consecutive columns of its row:
+    // one 16-byte store (and one 16-byte mask load) per column tile.
+    const int64_t m = tile * 16 + c;
+    if (m < a.M) {
+      const bool masked = Mk != nullptr && m < a.mask_rows;
+#pragma unroll
+      for (int t0 = 0; t0 < NT; t0 += TC) {
+        if (!kPrefetchMask) load_m(tile, t0, keep);
+#pragma unroll
+        for (int t = 0; t < TC; ++t) {
+          if (t0 + t >= NT) continue;
+          const int n = (t0 + t) * 16 + 4 * q;
+          if (n >= a.N) continue;
+          float v[4], pre[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            pre[r] = acc[t0 + t][r] + ((a.bias && n + r < a.N) ? a.bias[n + r] : 0.f);
+            v[r] = a.relu ? (pre[r] > 0.f ? pre[r] : 0.f) : pre[r];
+            if (masked) v[r] = keep[t][r] > 0.f ? v[r] : 0.f;
+          }
+          if (C2) store_quad<T>(C2 + m * a.ldc2, n, a.N, a.vecC2 == 4, pre);
+          store_quad<T>(C + m * a.ldc, n, a.N, a.vecC == 4, v);
+        }
+      }
+    }
+  }
+}
+
+static int nn_tiles(int N) { return N <= 16 ? 1 : N <= 32 ? 2 : N <= 48 ? 3 : N <= 64 ? 4 : N <= 128 ? 8 : 16; }
+
+size_t gemm_nn_direct_lds_bytes(int N, int K) {
+  return sizeof(float) * (size_t)((K + 15) & ~15) * (size_t)(nn_tiles(N) * 16 + 4);
+}
+
+bool gemm_nn_direct_ok(int N, int K) { return N <= 256 && gemm_nn_direct_lds_bytes(N, K) <= 128 * 1024; }
+
+template <typename T, int NT>
+static int nn_launch(const NnDirectArgs& a, hipStream_t s) {
+  const size_t lds = gemm_nn_direct_lds_bytes(a.N, a.K);
+  auto kern = k_gemm_nn_direct<T, NT>;
+  GCN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  const int64_t ntiles = ceil_div(a.M, 16);
+  const int per_cu = lds > 80 * 1024 ? 1 : 2;         // blocks that fit one compute unit's LDS
+  int64_t blocks = ceil_div(ntiles, kNnThreads / 64);
+  if (blocks > 256 * per_cu) blocks = 256 * per_cu;
+  kern<<<dim3((unsigned)blocks), dim3(kNnThreads), lds, s>>>(a);
+  GCN_CHECK_LAUNCH();
+  return GCN_OK;
+}
+
+template <typename T>
+static int nn_dispatch(const NnDirectArgs& a, hipStream_t s) {
+  switch (nn_tiles(a.N)) {
+    case 1: return nn_launch<T, 1>(a, s);
+    case 2: return nn_launch<T, 2>(a, s);
+    case 3: return nn_launch<T, 3>(a, s);
+    case 4: return nn_launch<T, 4>(a, s);
+    case 8: return nn_launch<T, 8>(a, s);
+    default: return nn_launch<T, 16>(a, s);
+  }
+}
+
+int gemm_nn_direct(const void* A, int64_t lda, const float* W, int64_t ldw, void* C, int64_t ldc, int64_t M, int N,
+                   int K, int dtype, const GemmEpilogue& epi, hipStream_t s) {
+  if (M == 0) return GCN_OK;
+  const size_t es = dtype == GCN_BF16 ? 2 : 4;
+  auto vec_of = [&](const void* p, int64_t ld) { return (p && (ld % 4) == 0 && ((uintptr_t)p % (4 * es)) == 0) ? 4 : 1; };
+  NnDirectArgs a{A, lda, W, ldw, C, ldc, M, N, K, vec_of(A, lda), vec_of(C, ldc), vec_of(epi.C2, epi.ldc2),
+                 vec_of(epi.mask, epi.ldmask),
+                 epi.bias, epi.relu, epi.mask, epi.ldmask, epi.mask_rows, epi.C2, epi.ldc2};
+  return dtype == GCN_BF16 ? nn_dispatch<bf16_t>(a, s) : nn_dispatch<float>(a, s);
+}
+
+// ------------------------------------------------------------------------------------------
+struct TnDirectArgs {
+  const void* A; int64_t lda; const void* B; int64_t ldb;
+  int64_t Kd; int M; int N; int64_t rows_per_split; int nsplit;
+  float* partial;   // [nsplit][M*N]
+};
+
+constexpr int kTnMaxUK = 8;       // most row pairs whose loads are issued together
+
+template <typename T, int TM, int TN, int kTnUK>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) void k_gemm_tn_direct(TnDirectArgs a) {
+  __shared__ float red[2][TM * TN * 16 * 64];
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = lane & 31, h = lane >> 5;
+  const int m0 = blockIdx.y * (32 * TM), n0 = blockIdx.z * (32 * TN);
+  const int64_t k_lo = (int64_t)blockIdx.x * a.rows_per_split;
+  const int64_t k_hi = k_lo + a.rows_per_split < a.Kd ? k_lo + a.rows_per_split : a.Kd;
+  const T* __restrict__ A = reinterpret_cast<const T*>(a.A);
+  const T* __restrict__ B = reinterpret_cast<const T*>(a.B);
+
+  // per-lane column offsets (clamped into the row so that every address is valid) and validity
+  int64_t aoff[TM], boff[TN];
+  bool aok[TM], bok[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) { const int m = m0 + 32 * i + c; aok[i] = m < a.M; aoff[i] = (int64_t)h * a.lda + (aok[i] ? m : 0); }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) { const int n = n0 + 32 * j + c; bok[j] = n < a.N; boff[j] = (int64_t)h * a.ldb + (bok[j] ? n : 0); }
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // wavefront w takes the chunks w, w + 4, ... of 2 * kTnUK rows
+  constexpr int CH = 2 * kTnUK;
+  for (int64_t k = k_lo + (int64_t)w * CH; k < k_hi; k += 4 * CH) {
+    float av[kTnUK][TM], bv[kTnUK][TN];
+    if (k + CH <= k_hi) {
+#pragma unroll
+      for (int u = 0; u < kTnUK; ++u) {
+        const T* __restrict__ ar = A + (k + 2 * u) * a.lda;
+        const T* __restrict__ br = B + (k + 2 * u) * a.ldb;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) av[u][i] = ldg<T>(ar + aoff[i]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bv[u][j] = ldg<T>(br + boff[j]);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kTnUK; ++u) {
+        const int64_t kr = k + 2 * u + h;
+        const bool rok = kr < k_hi;
+        const int64_t kc = rok ? k + 2 * u : k_lo - h;       // kc + h stays inside [k_lo, k_hi)
+        const T* __restrict__ ar = A + kc * a.lda;
+        const T* __restrict__ br = B + kc * a.ldb;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) { const float v = ldg<T>(ar + aoff[i]); av[u][i] = rok ? v : 0.f; }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) { const float v = ldg<T>(br + boff[j]); bv[u][j] = rok ? v : 0.f; }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kTnUK; ++u) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) { if (!aok[i]) av[u][i] = 0.f; }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) { if (!bok[j]) bv[u][j] = 0.f; }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][i], bv[u][j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // add the four wavefronts' tiles: (2,3) -> LDS -> (0,1) add; 1 -> LDS -> 0 adds
+  auto dump = [&](float* buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) buf[((i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+  };
+  auto take = [&](const float* buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] += buf[((i * TN + j) * 16 + r) * 64 + lane];
+  };
+  if (w >= 2) dump(red[w - 2]);
+  __syncthreads();
+  if (w < 2) take(red[w]);
+  __syncthreads();
+  if (w == 1) dump(red[0]);
+  __syncthreads();
+  if (w != 0) return;
+  take(red[0]);
+  float* __restrict__ P = a.partial + (int64_t)blockIdx.x * a.M * a.N;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = n0 + 32 * j + c;
+      if (n >= a.N) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + 32 * i + 8 * (r / 4) + 4 * h + (r % 4);
+        if (m < a.M) P[(int64_t)m * a.N + n] = acc[i][j][r];
+      }
+    }
+}
+
+static int tn_direct_tn(int N) { return N <= 32 ? 1 : 2; }
+
+static int tn_direct_splits(int64_t Kd, int M, int N) {
+  const int64_t tiles = ceil_div(M, 64) * ceil_div(N, 32 * tn_direct_tn(N));
+  int64_t want = ceil_div(1024, tiles);                // about four blocks per compute unit
+  int64_t max_by_k = ceil_div(Kd, 512);                // at least 512 rows per block
+  int64_t ns = want < max_by_k ? want : max_by_k;
+  return (int)(ns < 1 ? 1 : ns);
+}
+
+size_t gemm_tn_direct_ws_bytes(int64_t Kd, int M, int N) {
+  return sizeof(float) * (size_t)tn_direct_splits(Kd, M, N) * (size_t)M * (size_t)N;
+}
+
+int gemm_tn_direct_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype,
+                            float* partial, int* nsplit_out, hipStream_t s) {
+  TnDirectArgs a{A, lda, B, ldb, Kd, M, N, 0, 0, partial};
+  a.nsplit = tn_direct_splits(Kd, M, N);
+  a.rows_per_split = round_up(ceil_div(Kd > 0 ? Kd : 1, a.nsplit), 2 * kTnMaxUK);
+  *nsplit_out = a.nsplit;
+  const int tn = tn_direct_tn(N);
+  dim3 grid((unsigned)a.nsplit, (unsigned)ceil_div(M, 64), (unsigned)ceil_div(N, 32 * tn));
+  if (dtype == GCN_BF16) {
+    if (tn == 1) k_gemm_tn_direct<bf16_t, 2, 1, 8><<<grid, 256, 0, s>>>(a);
+    else k_gemm_tn_direct<bf16_t, 2, 2, 4><<<grid, 256, 0, s>>>(a);
+  } else {
+    if (tn == 1) k_gemm_tn_direct<float, 2, 1, 8><<<grid, 256, 0, s>>>(a);
+    else k_gemm_tn_direct<float, 2, 2, 4><<<grid, 256, 0, s>>>(a);
+  }
+  GCN_CHECK_LAUNCH();
+  return GCN_OK;
+}
+
+}  // namespace gcn
