@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/gcn.h"
 
 namespace gcn {
@@ -41,6 +43,23 @@ struct ProfScope {
   hipStream_t s_;
 };
 
+// RAII device buffer so that every error path frees what it allocated.
+struct DevBuf {
+  void* p = nullptr;
+  DevBuf() = default;
+  DevBuf(const DevBuf&) = delete;
+  DevBuf& operator=(const DevBuf&) = delete;
+  ~DevBuf() { if (p) (void)hipFree(p); }
+  int alloc(size_t bytes) {
+    if (p) { (void)hipFree(p); p = nullptr; }
+    hipError_t e = hipMalloc(&p, bytes ? bytes : 256);
+    if (e != hipSuccess) { p = nullptr; return fail(GCN_ENOMEM, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e)); }
+    return GCN_OK;
+  }
+  template <class T> T* as() const { return (T*)p; }
+  void* release() { void* q = p; p = nullptr; return q; }
+};
+
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 
@@ -66,6 +85,37 @@ struct Schedule {
   int64_t class_begin[34] = {0};
 };
 
+// ---- panel plan: the column-sweep execution layout of a sparse matrix (spmm_panel.hip) -------
+// Rows are cut into "virtual rows" of at most part_len entries (entry k of a row with P parts
+// belongs to part k % P); consecutive rows are packed into panels of at most nv_max virtual rows
+// whose accumulators fit in one workgroup's LDS.  A workgroup has kPanelWaves wavefronts of
+// 64 / lpg lane groups; every lane group owns some virtual rows of the panel (dealt out so that all
+// groups get about the same number of entries) and reads its own stream of entries, sorted by
+// (column block, virtual row, column).  The streams of the groups of one wavefront are stored
+// interleaved in batches of 8 entries per group, padded with kNoEntry where a stream has ended.
+constexpr int kPanelWaves = 16;
+constexpr int kPanelLists = 8;      // one work list per XCD
+struct PanelPlan {
+  bool transposed = false;
+  int ns = 1;              // feature slices (32 wide) the panel size was chosen for
+  int sw = 32;             // accumulator floats per virtual row: 32, or 16 for products of width <= 16
+  int lpg = 8;             // lanes per group
+  int cb_shift = 14;       // log2(columns per column block)
+  int part_len = 512;
+  int nv_max = 0;          // most virtual rows in one panel
+  int n_panels = 0;
+  int64_t n_rows = 0, total_vrows = 0, n_batches = 0;
+  uint2* ent = nullptr;           // [n_batches * 8 * (64 / lpg)] {index in owner << 24 | column, value bits}
+  int64_t* wb = nullptr;          // [n_panels * kPanelWaves + 1] first batch of each wavefront
+  int32_t* nfull = nullptr;       // [n_panels * kPanelWaves] leading batches without padding
+  int32_t* obase = nullptr;       // [n_panels * kPanelWaves * (64 / lpg)] first accumulator row of each group
+  int32_t* panel_row0 = nullptr;  // [n_panels + 1] first row of each panel
+  int32_t* row_v = nullptr;       // [n_rows + 1] index of the first virtual row of each row
+  int32_t* vlds = nullptr;        // [total_vrows] accumulator row of each virtual row inside its panel
+  int32_t* order = nullptr;       // [n_panels] panels by falling entry count
+  uint32_t* ctr = nullptr;        // [2 * kPanelLists] per-launch work counters
+};
+
 }  // namespace gcn
 
 // ---- the opaque handle -------------------------------------------------------------------
@@ -85,6 +135,7 @@ struct gcn_csr {
   gcn::Schedule sched_t;   // for A^T (rows = local columns)
   void* ws = nullptr;      // scratch workspace, grown on demand
   size_t ws_bytes = 0;
+  std::vector<gcn::PanelPlan*> plans;   // column-sweep layouts, built on first use (spmm_panel.hip)
 };
 
 namespace gcn {
@@ -126,10 +177,17 @@ struct SpmmArgs {
   // true when every row of X, the last one included, is backed by ldx readable elements (library
   // buffers with a padded leading dimension): vector loads may then run past column d
   bool x_rows_padded = false;
+  gcn_csr* owner = nullptr;  // handle the arrays belong to (lets the launch cache a panel plan); may be null
 };
 // ws: workspace for hub partial sums, at least spmm_ws_bytes(sched, d)
 size_t spmm_ws_bytes(const Schedule* sc, int d);
 int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s);
+// column-sweep variant (spmm_panel.hip): *used = false when the product does not qualify and
+// nothing was enqueued
+int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used);
+void free_panel_plans(gcn_csr* A);
+// ptr[q] = first position whose key >> shift is >= q, q in [0, n_seg]; keys sorted, n >= 1
+int segment_boundaries(const uint64_t* keys, int64_t n, int shift, int64_t n_seg, int64_t* ptr, hipStream_t s);
 
 struct GemmEpilogue {
   const float* bias = nullptr;   // [N] added to every row

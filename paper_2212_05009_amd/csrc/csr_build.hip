@@ -7,20 +7,6 @@
 
 namespace gcn {
 
-// RAII device buffer so that every error path frees what it allocated.
-struct DevBuf {
-  void* p = nullptr;
-  ~DevBuf() { if (p) (void)hipFree(p); }
-  int alloc(size_t bytes) {
-    if (p) { (void)hipFree(p); p = nullptr; }
-    hipError_t e = hipMalloc(&p, bytes ? bytes : 256);
-    if (e != hipSuccess) { p = nullptr; return fail(GCN_ENOMEM, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e)); }
-    return GCN_OK;
-  }
-  template <class T> T* as() const { return (T*)p; }
-  void* release() { void* q = p; p = nullptr; return q; }
-};
-
 constexpr int kThreads = 256;
 static inline unsigned grid_for(int64_t n) { return (unsigned)ceil_div(n > 0 ? n : 1, kThreads); }
 
@@ -408,6 +394,13 @@ static int build_impl(const int32_t* d_src, const int32_t* d_dst, int64_t n_edge
   return GCN_OK;
 }
 
+int segment_boundaries(const uint64_t* keys, int64_t n, int shift, int64_t n_seg, int64_t* ptr, hipStream_t s) {
+  if (n < 1) return fail(GCN_EINVAL, "segment_boundaries: empty input");
+  k_boundaries<<<grid_for(n), kThreads, 0, s>>>(keys, n, shift, n_seg, ptr);
+  GCN_CHECK_LAUNCH();
+  return GCN_OK;
+}
+
 int ensure_workspace(gcn_csr* A, size_t bytes) {
   if (bytes <= A->ws_bytes) return GCN_OK;
   if (A->ws) {
@@ -479,6 +472,7 @@ extern "C" int gcn_csr_free(gcn_csr_t* A) {
   for (void* p : ptrs) if (p) (void)hipFree(p);
   free_schedule(&A->sched);
   free_schedule(&A->sched_t);
+  free_panel_plans(A);
   delete A;
   return GCN_OK;
 }

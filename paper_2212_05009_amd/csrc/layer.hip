@@ -48,6 +48,7 @@ extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
       if (pass) {
         SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, H, ldh, AH, d_in, nullptr, 0,
                     d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+        sp.owner = Am;
         GCN_TRY(spmm_launch(sp, hub, s));
         GemmEpilogue epi;
         epi.bias = bias; epi.relu = relu; epi.C2 = Z; epi.ldc2 = d_out;
@@ -61,6 +62,7 @@ extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
         GCN_TRY(gemm_nn(H, ldh, W, d_out, P, ldp, A->nc, d_out, d_in, dtype, epi, s));
         SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, P, ldp, Hout, d_out, Z, d_out,
                     d_out, dtype, relu ? GCN_EPI_RELU : GCN_EPI_NONE, bias, nullptr, 0};
+        sp.owner = Am;
         sp.x_rows_padded = true;
         GCN_TRY(spmm_launch(sp, hub, s));
       }
@@ -103,6 +105,7 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
       if (pass) {
         SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, G, d_out, T, ldt, nullptr, 0,
                     d_out, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+        sp.owner = Am;
         GCN_TRY(spmm_launch(sp, hub, s));
         if (dH) {
           GCN_TRY(transpose_f32(W, d_in, d_out, Wt, s));
@@ -125,6 +128,7 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
           GCN_TRY(gemm_nn(G, d_out, Wt, d_in, Q, ldq, A->nr, d_in, d_out, dtype, epi, s));
           SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, Q, ldq, dH, d_in, nullptr, 0,
                       d_in, dtype, Zprev ? GCN_EPI_MASK : GCN_EPI_NONE, nullptr, Zprev, d_in};
+          sp.owner = Am;
           sp.x_rows_padded = true;
           GCN_TRY(spmm_launch(sp, hub, s));
         }
@@ -132,6 +136,7 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
         if (!AH_saved) {
           SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, H, ldh, AH, ldq, nullptr, 0,
                       d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+          sp.owner = Am;
           GCN_TRY(spmm_launch(sp, hub, s));
           ah = AH; ldah = ldq;
         }

@@ -53,6 +53,9 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
   k.bias = a.bias; k.Zprev = a.Zprev; k.ldz = a.ldz; k.n_mask_rows = a.n_mask_rows;
   k.partial = (float*)ws; k.d = a.d; k.epilogue = a.epilogue;
   if (a.n_rows == 0) return GCN_OK;
+  bool swept = false;
+  GCN_TRY(spmm_panel_try(a, s, &swept));
+  if (swept) return GCN_OK;
   const size_t es = a.dtype == GCN_BF16 ? 2 : 4;
   // widest vector such that every feature-row load stays aligned (and inside the row's storage)
   int V = a.dtype == GCN_BF16 ? 8 : 4;
@@ -98,6 +101,7 @@ extern "C" int gcn_spmm(const gcn_csr_t* A, const void* X, int64_t ldx, int d, i
   GCN_TRY(ensure_workspace(Am, spmm_ws_bytes(&A->sched, d)));
   SpmmArgs a{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, X, ldx, Y, ldy, nullptr, 0,
              d, dtype, epilogue, bias, Zprev, ldz};
+  a.owner = Am;
   return spmm_launch(a, Am->ws, (hipStream_t)stream);
 }
 
@@ -113,5 +117,6 @@ extern "C" int gcn_spmm_t(const gcn_csr_t* A, const void* X, int64_t ldx, int d,
   GCN_TRY(ensure_workspace(Am, spmm_ws_bytes(&A->sched_t, d)));
   SpmmArgs a{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, X, ldx, Y, ldy, nullptr, 0,
              d, dtype, epilogue, nullptr, Zprev, ldz};
+  a.owner = Am;
   return spmm_launch(a, Am->ws, (hipStream_t)stream);
 }

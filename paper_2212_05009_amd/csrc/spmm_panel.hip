@@ -1,0 +1,616 @@
+// Column-sweep variant of Y = epilogue(A X) for matrices whose dense operand is re-read many
+// times but does not fit the 4 MB L2 of an XCD (gfx950: 8 XCDs x 32 CUs, 160 KB LDS per CU).
+//
+// Sec. 4.1 defines the row task  Y(i,:) = sum_j A(i,j) X(j,:).  The row-per-wavefront kernel of
+// spmm_kernel.h gathers the rows X(j,:) in whatever order the rows i come, so most gathers of a
+// large X miss L2 and the kernel runs at the speed of the fabric behind L2.  Here the roles are
+// swapped: the OUTPUT rows of a panel (about a thousand rows, one 32-feature slice) stay in the
+// LDS of one workgroup, and the workgroup walks the panel's entries sorted by column block, so
+// at any time all 32 workgroups of an XCD gather from the same few column blocks of one feature
+// slice, which L2 holds.  A persistent grid (one workgroup per CU) takes (slice, panel) units
+// from one list per XCD; the k-th unit of a list starts when all units before round k / 32 are
+// done, which keeps the sweeps of an XCD in step (a bounded wait: only speed depends on it).
+//
+// Rows longer than part_len entries are dealt round-robin to several "virtual rows", each with
+// its own LDS accumulator, so that no row is a load-balance problem; the parts are added in
+// order when the panel is written out.  Every virtual row is owned by one lane group of one
+// wavefront: the group adds a run of entries in registers and then into the accumulator with a
+// plain read-add-write, no atomics, so results are bitwise reproducible.
+#include <stdio.h>
+#include <stdlib.h>
+
+#include <algorithm>
+#include <new>
+#include <queue>
+#include <utility>
+#include <vector>
+
+#include "spmm_kernel.h"
+
+namespace gcn {
+
+namespace {
+
+constexpr int kLidBits = 8;                // index of a virtual row among those of its lane group
+constexpr int kMaxLid = 254;
+constexpr int kColBits = 24;               // column id
+constexpr uint32_t kNoEntry = 0xffffffffu;
+constexpr int kPanelThreads = 64 * kPanelWaves;
+constexpr int kLdsBudget = 152 * 1024;     // accumulator bytes per workgroup (of 160 KB)
+constexpr int kMaxVrows = 2047;
+constexpr int kMaxSpins = 20000;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct PanelK {
+  SpmmK k;                       // X, Y and epilogue fields
+  const uint2* ent; const int64_t* wb; const int32_t* nfull; const int32_t* obase;
+  const int32_t* panel_row0; const int32_t* row_v; const int32_t* vlds; const int32_t* order;
+  uint32_t* ctr;                 // [0, kPanelLists): next unit of each list; [kPanelLists, 2 kPanelLists): units done
+  int n_panels, ns;
+  int q;                         // > 0: q lists share a slice (list = slice * q + a takes panels a, a + q, ...)
+  int list_begin[kPanelLists];   // q == 0: list i holds the units [list_begin[i], list_begin[i] + list_len[i]) of the
+  int list_len[kPanelLists];     //         slice-major enumeration unit = slice * n_panels + position
+  int wg_per_list;
+};
+
+__global__ void k_panel_reset(uint32_t* ctr) {
+  if (threadIdx.x < 2 * kPanelLists) ctr[threadIdx.x] = 0u;
+}
+
+// ---- plan construction kernels ---------------------------------------------------------------
+// key = owner << (cbbits + 8) | column block << 8 | index of the virtual row in its owner
+__global__ void k_plan_keys(const int64_t* __restrict__ ptr, int64_t n_rows, int64_t nnz,
+                            const int32_t* __restrict__ idx, int part_len, const int32_t* __restrict__ row_v,
+                            const uint32_t* __restrict__ vinfo, int cb_shift, int cbbits,
+                            uint64_t* __restrict__ keys, uint32_t* __restrict__ pay) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= nnz) return;
+  int64_t lo = 0, hi = n_rows;             // last row r with ptr[r] <= p
+  while (hi - lo > 1) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (ptr[mid] <= p) lo = mid; else hi = mid;
+  }
+  const int64_t r = lo;
+  const int64_t s = ptr[r], len = ptr[r + 1] - s;
+  const int64_t parts = len <= part_len ? 1 : (len + part_len - 1) / part_len;
+  const uint32_t info = vinfo[row_v[r] + (p - s) % parts];      // owner << 8 | index in owner
+  const uint64_t cb = (uint64_t)(idx[p] >> cb_shift);
+  keys[p] = ((uint64_t)(info >> kLidBits) << (cbbits + kLidBits)) | (cb << kLidBits) | (uint64_t)(info & 0xffu);
+  pay[p] = (uint32_t)p;
+}
+
+// batches of each wavefront: enough for its longest group stream; nfull = batches every group fills
+__global__ void k_plan_waves(const int64_t* __restrict__ oseg, int64_t n_waves, int groups,
+                             uint32_t* __restrict__ nb, int32_t* __restrict__ nfull) {
+  const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= n_waves) return;
+  int64_t mx = 0, mn = INT64_MAX;
+  for (int g = 0; g < groups; ++g) {
+    const int64_t len = oseg[w * groups + g + 1] - oseg[w * groups + g];
+    mx = len > mx ? len : mx; mn = len < mn ? len : mn;
+  }
+  nb[w] = (uint32_t)((mx + 7) / 8);
+  nfull[w] = (int32_t)(mn / 8);
+}
+
+__global__ void k_plan_fill_pad(uint2* __restrict__ ent, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) ent[i] = make_uint2(kNoEntry, 0u);
+}
+
+__global__ void k_plan_scatter(const uint64_t* __restrict__ keys, const uint32_t* __restrict__ pay,
+                               const int32_t* __restrict__ idx, const float* __restrict__ val, int64_t nnz,
+                               int shift, int groups, const int64_t* __restrict__ oseg,
+                               const int64_t* __restrict__ wb, uint2* __restrict__ ent) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= nnz) return;
+  const uint64_t key = keys[q];
+  const int64_t o = (int64_t)(key >> shift);
+  const int64_t k = q - oseg[o];
+  const int64_t w = o / groups, g = o % groups;
+  const int64_t pos = (wb[w] + k / 8) * (8 * groups) + g * 8 + k % 8;
+  const uint32_t p = pay[q];
+  ent[pos] = make_uint2(((uint32_t)(key & 0xffu) << kColBits) | (uint32_t)idx[p], __float_as_uint(val[p]));
+}
+
+// ---- the product kernel --------------------------------------------------------------------------
+template <int EPL>
+__device__ __forceinline__ void load_entries(const uint2* __restrict__ ent, int64_t batch, int batch_entries, int lane,
+                                             uint32_t (&e)[2 * EPL]) {
+  const uint2* p = ent + batch * batch_entries + lane * EPL;
+  if constexpr (EPL == 1) {
+    const u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+    e[0] = t.x; e[1] = t.y;
+  } else {
+#pragma unroll
+    for (int i = 0; i < EPL / 2; ++i) {
+      const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p) + i);
+      e[4 * i] = t.x; e[4 * i + 1] = t.y; e[4 * i + 2] = t.z; e[4 * i + 3] = t.w;
+    }
+  }
+}
+
+// entry i of lane group g of the batch held in e (every lane of the group gets it)
+template <int LPG>
+__device__ __forceinline__ uint32_t group_entry(const uint32_t (&e)[2 * (8 / LPG)], int g, int i, int word) {
+  constexpr int EPL = 8 / LPG;
+  return (uint32_t)__builtin_amdgcn_ds_bpermute((g * LPG + i / EPL) << 2, (int)e[2 * (i % EPL) + word]);
+}
+
+// puts the 8 gathers of this lane group's entries in flight (kept as loaded: 16 bytes each)
+template <typename T, int V, int LPG, bool CHECK>
+__device__ __forceinline__ void issue_batch(const uint32_t (&e)[2 * (8 / LPG)], int g, const char* xb, uint32_t row_bytes,
+                                            uint32_t xoff, typename Vec<T, V>::type (&x)[8]) {
+  uint32_t c[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) c[i] = group_entry<LPG>(e, g, i, 0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (CHECK) c[i] = c[i] == kNoEntry ? 0u : c[i];     // padding gathers row 0 (a valid address), and is dropped later
+    const uint32_t off = __umul24(c[i], row_bytes) + xoff;
+    x[i] = *reinterpret_cast<const typename Vec<T, V>::type*>(xb + off);
+  }
+}
+
+template <int V>
+__device__ __forceinline__ void add_to_row(float* __restrict__ row, const float (&av)[V]) {
+#pragma unroll
+  for (int v0 = 0; v0 < V; v0 += 4) {
+    float4 t = *reinterpret_cast<float4*>(row + v0);
+    t.x += av[v0]; t.y += av[v0 + 1]; t.z += av[v0 + 2]; t.w += av[v0 + 3];
+    *reinterpret_cast<float4*>(row + v0) = t;
+  }
+}
+
+// e: the entries the batch was issued from (index and value are fetched from the owning lanes again)
+template <typename T, int V, int LPG, bool CHECK>
+__device__ __forceinline__ void consume_batch(const uint32_t (&e)[2 * (8 / LPG)], int g,
+                                              const typename Vec<T, V>::type (&x)[8], float* __restrict__ myacc,
+                                              bool active, int& cur, float (&av)[V]) {
+  constexpr int SW = V * LPG;
+  // all sixteen cross-lane reads go out before the first is used: one LDS round trip per batch, not per entry
+  uint32_t pks[8]; float ws[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { pks[i] = group_entry<LPG>(e, g, i, 0); ws[i] = __uint_as_float(group_entry<LPG>(e, g, i, 1)); }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const uint32_t pk = pks[i];
+    const float w = ws[i];
+    const bool valid = !CHECK || pk != kNoEntry;
+    const int lid = (int)(pk >> kColBits);
+    if (valid && lid != cur) {
+      if (cur >= 0 && active) add_to_row<V>(myacc + cur * SW, av);
+#pragma unroll
+      for (int v = 0; v < V; ++v) av[v] = 0.f;
+      cur = lid;
+    }
+    const T* xe = reinterpret_cast<const T*>(&x[i]);
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      float xv;
+      if constexpr (sizeof(T) == 4) xv = (float)xe[v]; else xv = bf16_to_f32((bf16_t)xe[v]);
+      if (CHECK) xv = valid ? xv : 0.f;
+      av[v] = fmaf(CHECK ? (valid ? w : 0.f) : w, xv, av[v]);
+    }
+  }
+}
+
+// batches [b0, b1) of one wavefront, two batches of gathers in flight.  Inside the loop there is no
+// conditional load between the gathers of a batch and their use, so the compiler's wait counts are
+// exact (the entries two batches ahead are always fetched, those of the last batch again at the end).
+template <typename T, int V, int LPG, bool CHECK>
+__device__ __forceinline__ void sweep(const uint2* __restrict__ ent, int64_t b0, int64_t b1, int lane, int g,
+                                      const char* xb, uint32_t row_bytes, uint32_t xoff, float* __restrict__ myacc,
+                                      bool active, int& cur, float (&av)[V]) {
+  constexpr int EPL = 8 / LPG, G = 64 / LPG, BATCH = 8 * G;
+  typedef typename Vec<T, V>::type XV;
+  if (b0 >= b1) return;
+  const int64_t last = b1 - 1;
+  uint32_t eA[2 * EPL], eB[2 * EPL], eC[2 * EPL];
+  XV xA[8], xB[8];
+  load_entries<EPL>(ent, b0, BATCH, lane, eA);
+  load_entries<EPL>(ent, b0 + 1 < last ? b0 + 1 : last, BATCH, lane, eB);
+  issue_batch<T, V, LPG, CHECK>(eA, g, xb, row_bytes, xoff, xA);
+  int64_t b = b0;
+  while (b + 2 <= last) {
+    // xA: gathers of batch b (entries eA) in flight; eB: entries of batch b + 1
+    load_entries<EPL>(ent, b + 2, BATCH, lane, eC);
+    issue_batch<T, V, LPG, CHECK>(eB, g, xb, row_bytes, xoff, xB);
+    consume_batch<T, V, LPG, CHECK>(eA, g, xA, myacc, active, cur, av);
+    load_entries<EPL>(ent, b + 3 < last ? b + 3 : last, BATCH, lane, eA);
+    issue_batch<T, V, LPG, CHECK>(eC, g, xb, row_bytes, xoff, xA);
+    consume_batch<T, V, LPG, CHECK>(eB, g, xB, myacc, active, cur, av);
+    b += 2;
+    // xA: gathers of batch b (entries eC) in flight; eA: entries of batch b + 1
+#pragma unroll
+    for (int i = 0; i < 2 * EPL; ++i) { const uint32_t t = eA[i]; eA[i] = eC[i]; eB[i] = t; }
+  }
+  if (b < last) issue_batch<T, V, LPG, CHECK>(eB, g, xb, row_bytes, xoff, xB);
+  consume_batch<T, V, LPG, CHECK>(eA, g, xA, myacc, active, cur, av);
+  if (b < last) consume_batch<T, V, LPG, CHECK>(eB, g, xB, myacc, active, cur, av);
+}
+
+template <typename T, int V, int LPG>
+__global__ __launch_bounds__(kPanelThreads) void k_spmm_panel(PanelK a) {
+  constexpr int G = 64 / LPG;
+  constexpr int SW = V * LPG;
+  static_assert(G * LPG == 64 && 8 % LPG == 0 && V % 4 == 0, "lane groups must tile the wavefront");
+  extern __shared__ __align__(16) float acc[];
+  __shared__ int s_unit[2];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane / LPG, l = lane % LPG;
+  uint32_t xcc;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+  int li = (int)(xcc & 15u) % kPanelLists;   // thread 0's list cursor
+  int tried = 0;
+
+  for (;;) {
+    if (tid == 0) {
+      int unit = -1, from = 0;
+      while (tried < kPanelLists) {
+        const int kk = (int)atomicAdd(&a.ctr[li], 1u);
+        if (kk < a.list_len[li]) { unit = kk; from = li; break; }
+        li = (li + 1) % kPanelLists;
+        ++tried;
+      }
+      if (unit >= 0) {
+        // start in step with the other workgroups of this list
+        const uint32_t target = (uint32_t)(unit / a.wg_per_list) * (uint32_t)a.wg_per_list;
+        const uint32_t* done = a.ctr + kPanelLists + from;
+        for (int spins = 0; spins < kMaxSpins; ++spins) {
+          if (__hip_atomic_load(done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) break;
+          __builtin_amdgcn_s_sleep(16);
+        }
+      }
+      s_unit[0] = unit; s_unit[1] = from;
+    }
+    __syncthreads();
+    const int unit = s_unit[0], from = s_unit[1];
+    if (unit < 0) break;
+    int slice, pos;
+    if (a.q > 0) { slice = from / a.q; pos = unit * a.q + from % a.q; }
+    else { const int u = a.list_begin[from] + unit; slice = u / a.n_panels; pos = u - slice * a.n_panels; }
+    const int panel = a.order[pos];
+    const int row0 = a.panel_row0[panel], row1 = a.panel_row0[panel + 1];
+    const int pv0 = a.row_v[row0];
+    const int nv = a.row_v[row1] - pv0;
+    for (int i = tid * 4; i < nv * SW; i += kPanelThreads * 4) *reinterpret_cast<float4*>(acc + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();
+
+    // ---- this wavefront's batches; lane group g adds into its own accumulator rows
+    {
+      const int64_t gw = (int64_t)panel * kPanelWaves + w;
+      const int64_t bb = a.wb[gw], be = a.wb[gw + 1];
+      const int64_t bf = bb + a.nfull[gw];
+      const int c0 = slice * 32 + l * V;
+      const bool active = c0 < a.k.d;
+      const uint32_t xoff = (uint32_t)((active ? c0 : slice * 32) * (int)sizeof(T));
+      const char* xb = reinterpret_cast<const char*>(a.k.X);
+      float* myacc = acc + a.obase[gw * G + g] * SW + l * V;
+      int cur = -1;
+      float av[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) av[v] = 0.f;
+      sweep<T, V, LPG, false>(a.ent, bb, bf, lane, g, xb, a.k.row_bytes, xoff, myacc, active, cur, av);
+      sweep<T, V, LPG, true>(a.ent, bf, be, lane, g, xb, a.k.row_bytes, xoff, myacc, active, cur, av);
+      if (cur >= 0 && active) add_to_row<V>(myacc + cur * SW, av);
+    }
+    __syncthreads();
+    if (tid == 0) __hip_atomic_fetch_add(a.ctr + kPanelLists + from, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    // ---- write the panel: add the parts of each row in order, apply the epilogue
+    const int n_el = (row1 - row0) * SW;
+    for (int i = tid; i < n_el; i += kPanelThreads) {
+      const int r = row0 + i / SW, f = i % SW;
+      const int c = slice * 32 + f;
+      if (c < a.k.d) {
+        const int v0 = a.row_v[r], v1 = a.row_v[r + 1];
+        float sum = 0.f;
+        for (int vg = v0; vg < v1; ++vg) sum += acc[a.vlds[vg] * SW + f];
+        finish_element<T>(a.k, r, c, sum);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+template <typename T, int V, int LPG>
+int launch_panel(const PanelK& k, int n_wg, size_t lds_bytes, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    GCN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&k_spmm_panel<T, V, LPG>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget));
+    attr_set = true;
+  }
+  k_spmm_panel<T, V, LPG><<<dim3((unsigned)n_wg), dim3(kPanelThreads), lds_bytes, s>>>(k);
+  GCN_CHECK_LAUNCH();
+  return GCN_OK;
+}
+
+int device_cus() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+    if (cus <= 0) cus = 256;
+  }
+  return cus;
+}
+
+void free_plan(PanelPlan* p) {
+  if (!p) return;
+  void* ptrs[] = {p->ent, p->wb, p->nfull, p->obase, p->panel_row0, p->row_v, p->vlds, p->order, p->ctr};
+  for (void* q : ptrs) if (q) (void)hipFree(q);
+  delete p;
+}
+
+int bits_for_count(int64_t n) { int b = 1; while ((1LL << b) < n) ++b; return b; }
+
+// Builds the layout for products with `ns` feature slices, `sw` accumulator floats per virtual
+// row and lane groups of `lpg` lanes.  *out stays null when the matrix does not fit the format.
+int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shift, hipStream_t s, PanelPlan** out) {
+  *out = nullptr;
+  const int64_t n = transposed ? A->nc : A->nr;
+  const int64_t nnz = A->nnz;
+  const int64_t* d_ptr = transposed ? A->colptr : A->rowptr;
+  const int32_t* d_idx = transposed ? A->rowidx : A->col;
+  const float* d_val = transposed ? A->val_t : A->val;
+  const int64_t n_cols = transposed ? A->nr : A->nc;
+  const int n_wg = device_cus();
+  const int groups = 64 / lpg;
+  const int n_own = kPanelWaves * groups;          // owners (lane groups) per panel
+
+  std::vector<int64_t> ptr((size_t)n + 1);
+  GCN_HIP(hipMemcpyAsync(ptr.data(), d_ptr, sizeof(int64_t) * (size_t)(n + 1), hipMemcpyDeviceToHost, s));
+  GCN_HIP(hipStreamSynchronize(s));
+
+  // ---- virtual rows and the panel size
+  const int cap = std::min(kMaxVrows, kLdsBudget / (sw * 4));
+  int64_t max_len = 0;
+  for (int64_t r = 0; r < n; ++r) max_len = std::max(max_len, ptr[r + 1] - ptr[r]);
+  // a part should be well below a lane group's share of a panel, or the groups cannot be balanced
+  int part_len = nnz / std::max<int64_t>(n, 1) < 128 ? 256 : 512;
+  int nv = cap;
+  int64_t total_v = 0;
+  for (;;) {
+    total_v = 0;
+    for (int64_t r = 0; r < n; ++r) {
+      const int64_t len = ptr[r + 1] - ptr[r];
+      total_v += len <= part_len ? 1 : ceil_div(len, part_len);
+    }
+    const int64_t max_parts = std::max<int64_t>(1, ceil_div(max_len, part_len));
+    // whole rounds of n_wg units: the fewest rounds whose panels fit the LDS, then the smallest
+    // panels that still need no more rounds
+    const int64_t rounds = std::max<int64_t>(1, ceil_div(total_v * ns * 103, (int64_t)n_wg * cap * 100));
+    const int64_t want_panels = std::max<int64_t>(1, (int64_t)n_wg * rounds / ns);
+    nv = (int)std::min<int64_t>(cap, ceil_div(total_v * 102, want_panels * 100) + 1);
+    if (max_parts * 2 <= nv || max_parts <= 1) break;
+    part_len *= 2;
+  }
+  if (total_v >= 0x7fffffffLL) return GCN_OK;
+
+  std::vector<int32_t> row_v((size_t)n + 1), panel_row0;
+  {
+    int64_t v = 0; int in_panel = 0;
+    panel_row0.push_back(0);
+    for (int64_t r = 0; r < n; ++r) {
+      const int64_t len = ptr[r + 1] - ptr[r];
+      const int parts = (int)(len <= part_len ? 1 : ceil_div(len, part_len));
+      if (in_panel + parts > nv && in_panel > 0) { panel_row0.push_back((int32_t)r); in_panel = 0; }
+      row_v[(size_t)r] = (int32_t)v;
+      v += parts; in_panel += parts;
+    }
+    row_v[(size_t)n] = (int32_t)v;
+    panel_row0.push_back((int32_t)n);
+  }
+  const int n_panels = (int)panel_row0.size() - 1;
+  if ((int64_t)n_panels * n_own >= (1LL << 24)) return GCN_OK;      // owner ids must fit 24 bits
+  int nv_max = 0;
+  for (int p = 0; p < n_panels; ++p)
+    nv_max = std::max(nv_max, row_v[(size_t)panel_row0[(size_t)p + 1]] - row_v[(size_t)panel_row0[(size_t)p]]);
+  if (nv_max > cap) return fail(GCN_EHIP, "panel plan: internal error (panel of %d virtual rows)", nv_max);
+
+  // ---- owner of each virtual row: longest first onto the least loaded lane group of the panel
+  std::vector<uint32_t> vinfo((size_t)total_v);
+  std::vector<int32_t> vlds((size_t)total_v), obase((size_t)n_panels * n_own);
+  std::vector<int64_t> panel_nnz((size_t)n_panels);
+  {
+    typedef std::pair<int64_t, int32_t> Load;           // (entries, virtual row) or (entries so far, owner)
+    std::vector<Load> vr;
+    std::vector<int32_t> cnt((size_t)n_own), owner_of;
+    for (int p = 0; p < n_panels; ++p) {
+      const int64_t r0 = panel_row0[(size_t)p], r1 = panel_row0[(size_t)p + 1];
+      const int32_t pv0 = row_v[(size_t)r0];
+      panel_nnz[(size_t)p] = ptr[r1] - ptr[r0];
+      vr.clear();
+      for (int64_t r = r0; r < r1; ++r) {
+        const int64_t len = ptr[r + 1] - ptr[r];
+        const int64_t parts = row_v[(size_t)r + 1] - row_v[(size_t)r];
+        for (int64_t j = 0; j < parts; ++j)
+          vr.emplace_back(j < len ? (len - j + parts - 1) / parts : 0, (int32_t)(row_v[(size_t)r] + j));
+      }
+      std::stable_sort(vr.begin(), vr.end(), [](const Load& x, const Load& y) { return x.first > y.first; });
+      std::priority_queue<Load, std::vector<Load>, std::greater<Load>> heap;
+      for (int o = 0; o < n_own; ++o) heap.emplace(0, o);
+      std::fill(cnt.begin(), cnt.end(), 0);
+      owner_of.assign(vr.size(), 0);
+      for (size_t i = 0; i < vr.size(); ++i) {
+        if (heap.empty()) return fail(GCN_EHIP, "panel plan: internal error (no lane group left)");
+        Load t = heap.top(); heap.pop();
+        owner_of[(size_t)(vr[i].second - pv0)] = t.second;
+        const int lid = cnt[(size_t)t.second]++;
+        vinfo[(size_t)vr[i].second] = (((uint32_t)p * (uint32_t)n_own + (uint32_t)t.second) << kLidBits) | (uint32_t)lid;
+        if (lid + 1 <= kMaxLid) heap.emplace(t.first + vr[i].first, t.second);
+      }
+      int32_t run = 0;
+      for (int o = 0; o < n_own; ++o) { obase[(size_t)p * n_own + o] = run; run += cnt[(size_t)o]; }
+      for (size_t i = 0; i < vr.size(); ++i) {
+        const int32_t vg = pv0 + (int32_t)i;
+        vlds[(size_t)vg] = obase[(size_t)p * n_own + owner_of[i]] + (int32_t)(vinfo[(size_t)vg] & 0xffu);
+      }
+    }
+  }
+  std::vector<int32_t> order((size_t)n_panels);
+  for (int p = 0; p < n_panels; ++p) order[(size_t)p] = p;
+  std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return panel_nnz[(size_t)x] > panel_nnz[(size_t)y]; });
+
+  // ---- device side: sort the entries into the interleaved group streams
+  PanelPlan* P = new (std::nothrow) PanelPlan();
+  if (!P) return fail(GCN_ENOMEM, "panel plan: host allocation failed");
+  struct Guard { PanelPlan* p; ~Guard() { if (p) free_plan(p); } } guard{P};
+  P->transposed = transposed; P->ns = ns; P->sw = sw; P->lpg = lpg; P->cb_shift = cb_shift; P->part_len = part_len;
+  P->nv_max = nv_max; P->n_panels = n_panels; P->n_rows = n; P->total_vrows = total_v;
+  auto dev_alloc = [&](void** p, size_t bytes) -> int {
+    hipError_t e = hipMalloc(p, bytes ? bytes : 256);
+    if (e != hipSuccess) { *p = nullptr; return fail(GCN_ENOMEM, "panel plan: hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e)); }
+    return GCN_OK;
+  };
+  const int64_t n_waves = (int64_t)n_panels * kPanelWaves, n_owners = (int64_t)n_panels * n_own;
+  GCN_TRY(dev_alloc((void**)&P->wb, sizeof(int64_t) * ((size_t)n_waves + 1)));
+  GCN_TRY(dev_alloc((void**)&P->nfull, sizeof(int32_t) * (size_t)n_waves));
+  GCN_TRY(dev_alloc((void**)&P->obase, sizeof(int32_t) * (size_t)n_owners));
+  GCN_TRY(dev_alloc((void**)&P->panel_row0, sizeof(int32_t) * ((size_t)n_panels + 1)));
+  GCN_TRY(dev_alloc((void**)&P->row_v, sizeof(int32_t) * ((size_t)n + 1)));
+  GCN_TRY(dev_alloc((void**)&P->vlds, sizeof(int32_t) * (size_t)total_v));
+  GCN_TRY(dev_alloc((void**)&P->order, sizeof(int32_t) * (size_t)n_panels));
+  GCN_TRY(dev_alloc((void**)&P->ctr, sizeof(uint32_t) * 2 * kPanelLists));
+  DevBuf d_vinfo, keys_a, keys_b, pay_a, pay_b, tmp, oseg, nb;
+  GCN_TRY(d_vinfo.alloc(sizeof(uint32_t) * (size_t)total_v));
+  GCN_TRY(keys_a.alloc(sizeof(uint64_t) * (size_t)nnz));
+  GCN_TRY(keys_b.alloc(sizeof(uint64_t) * (size_t)nnz));
+  GCN_TRY(pay_a.alloc(sizeof(uint32_t) * (size_t)nnz));
+  GCN_TRY(pay_b.alloc(sizeof(uint32_t) * (size_t)nnz));
+  GCN_TRY(oseg.alloc(sizeof(int64_t) * ((size_t)n_owners + 1)));
+  GCN_TRY(nb.alloc(sizeof(uint32_t) * (size_t)n_waves));
+  size_t tb = sort_tmp_bytes(nnz);
+  if (scan_tmp_bytes(n_waves) > tb) tb = scan_tmp_bytes(n_waves);
+  GCN_TRY(tmp.alloc(tb));
+  GCN_HIP(hipMemcpyAsync(P->panel_row0, panel_row0.data(), sizeof(int32_t) * ((size_t)n_panels + 1), hipMemcpyHostToDevice, s));
+  GCN_HIP(hipMemcpyAsync(P->row_v, row_v.data(), sizeof(int32_t) * ((size_t)n + 1), hipMemcpyHostToDevice, s));
+  GCN_HIP(hipMemcpyAsync(P->order, order.data(), sizeof(int32_t) * (size_t)n_panels, hipMemcpyHostToDevice, s));
+  GCN_HIP(hipMemcpyAsync(P->vlds, vlds.data(), sizeof(int32_t) * (size_t)total_v, hipMemcpyHostToDevice, s));
+  GCN_HIP(hipMemcpyAsync(P->obase, obase.data(), sizeof(int32_t) * (size_t)n_owners, hipMemcpyHostToDevice, s));
+  GCN_HIP(hipMemcpyAsync(d_vinfo.p, vinfo.data(), sizeof(uint32_t) * (size_t)total_v, hipMemcpyHostToDevice, s));
+  const int cbbits = bits_for_count(ceil_div(n_cols, (int64_t)1 << cb_shift));
+  const int ownbits = bits_for_count(n_owners);
+  if (kLidBits + cbbits + ownbits > 64) return GCN_OK;
+  const unsigned grid = (unsigned)ceil_div(nnz, 256);
+  k_plan_keys<<<grid, 256, 0, s>>>(d_ptr, n, nnz, d_idx, part_len, P->row_v, d_vinfo.as<uint32_t>(), cb_shift, cbbits,
+                                   keys_a.as<uint64_t>(), pay_a.as<uint32_t>());
+  GCN_CHECK_LAUNCH();
+  uint64_t* sorted = nullptr; uint32_t* spay = nullptr;
+  GCN_TRY(radix_sort_u64(keys_a.as<uint64_t>(), keys_b.as<uint64_t>(), pay_a.as<uint32_t>(), pay_b.as<uint32_t>(), nnz, 0,
+                         kLidBits + cbbits + ownbits, tmp.p, s, &sorted, &spay));
+  GCN_TRY(segment_boundaries(sorted, nnz, kLidBits + cbbits, n_owners, oseg.as<int64_t>(), s));
+  k_plan_waves<<<(unsigned)ceil_div(n_waves, 256), 256, 0, s>>>(oseg.as<int64_t>(), n_waves, groups, nb.as<uint32_t>(), P->nfull);
+  GCN_CHECK_LAUNCH();
+  GCN_TRY(exclusive_scan_u32(nb.as<uint32_t>(), P->wb, n_waves, tmp.p, s));
+  int64_t n_batches = 0;
+  GCN_HIP(hipMemcpyAsync(&n_batches, P->wb + n_waves, sizeof(int64_t), hipMemcpyDeviceToHost, s));
+  GCN_HIP(hipStreamSynchronize(s));
+  P->n_batches = n_batches;
+  const int64_t n_ent = n_batches * 8 * groups;
+  GCN_TRY(dev_alloc((void**)&P->ent, sizeof(uint2) * (size_t)n_ent));
+  if (n_ent > 0) k_plan_fill_pad<<<(unsigned)ceil_div(n_ent, 256), 256, 0, s>>>(P->ent, n_ent);
+  k_plan_scatter<<<grid, 256, 0, s>>>(sorted, spay, d_idx, d_val, nnz, kLidBits + cbbits, groups, oseg.as<int64_t>(), P->wb, P->ent);
+  GCN_CHECK_LAUNCH();
+  GCN_HIP(hipStreamSynchronize(s));      // host vectors and temporaries go out of scope
+  if (getenv("GCN_PANEL_VERBOSE"))
+    fprintf(stderr, "[panel plan] rows %lld nnz %lld ns %d sw %d lpg %d cb_shift %d part_len %d vrows %lld panels %d nv_max %d batches %lld (padding %.1f%%)\n",
+            (long long)n, (long long)nnz, ns, sw, lpg, cb_shift, part_len, (long long)total_v, n_panels, nv_max,
+            (long long)n_batches, 100.0 * ((double)n_ent / (double)nnz - 1.0));
+  guard.p = nullptr;
+  *out = P;
+  return GCN_OK;
+}
+
+}  // namespace
+
+void free_panel_plans(gcn_csr* A) {
+  for (PanelPlan* p : A->plans) free_plan(p);
+  A->plans.clear();
+}
+
+int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used) {
+  *used = false;
+  const char* env = getenv("GCN_SPMM_PANEL");            // 0: never, 1: whenever the limits allow
+  const int force = env ? atoi(env) : -1;
+  if (force == 0 || !a.owner || a.n_rows < 1 || a.nnz < 1) return GCN_OK;
+  const size_t es = a.dtype == GCN_BF16 ? 2 : 4;
+  // limits of the packed entry format and of 32-bit addressing of X
+  const double xspan = (double)a.n_cols * (double)a.ldx * (double)es;
+  if (a.n_cols >= (1 << kColBits) - 1 || a.ldx * (int64_t)es >= (1 << 24) || xspan >= 4294967296.0 || a.nnz >= 0xffffffffLL)
+    return GCN_OK;
+  // the gathers are 16-byte vector loads
+  auto aligned = [](const void* p, size_t al) { return ((uintptr_t)p % al) == 0; };
+  const int V = a.dtype == GCN_BF16 ? 8 : 4;
+  if (!((a.ldx % V) == 0 && aligned(a.X, 16) && ((a.d % V) == 0 || a.x_rows_padded))) return GCN_OK;
+  const int sw = a.d <= 16 ? 16 : 32;
+  const int lpg = sw / V;
+  const int ns = sw == 16 ? 1 : (int)ceil_div(a.d, 32);
+  // bytes of L2 one row of the operand occupies in an XCD that works on one slice
+  const double foot = ns == 1 ? (double)a.d * (double)es : 128.0;
+  int cb_shift = 10;
+  while (cb_shift < 20 && (double)(2LL << cb_shift) * foot <= 2.0 * 1024 * 1024) ++cb_shift;
+  const int n_wg = device_cus();
+  if (force != 1) {
+    // Worth it when the gathers of one round re-read the operand many times and the operand does not
+    // sit in L2 anyway.  Measured (fp32, width 128): 1.7x faster than the row-per-wavefront kernel at
+    // reuse 80 (233 k rows, 490 entries per row), 1.2x slower at reuse 6 (262 k rows, 45 per row),
+    // where the longer instruction stream per entry costs more than the saved L2 misses.  The bf16
+    // instances need more registers than a 16-wave workgroup leaves them: row-per-wavefront for now.
+    const int cap = std::min(kMaxVrows, kLdsBudget / (sw * 4));
+    const double reuse = (double)(n_wg / kPanelLists) * cap * ((double)a.nnz / (double)a.n_rows) / (double)a.n_cols;
+    if (a.dtype != GCN_F32 || a.nnz < (1 << 20) || (double)a.n_cols * foot < 6.0 * 1024 * 1024 || reuse < 20.0) return GCN_OK;
+  }
+
+  PanelPlan* P = nullptr;
+  for (PanelPlan* p : a.owner->plans)
+    if (p->transposed == a.transposed && p->ns == ns && p->sw == sw && p->lpg == lpg && p->cb_shift == cb_shift) { P = p; break; }
+  if (!P) {
+    GCN_TRY(build_plan(a.owner, a.transposed, ns, sw, lpg, cb_shift, s, &P));
+    if (!P) return GCN_OK;
+    a.owner->plans.push_back(P);
+  }
+
+  PanelK k;
+  k.k.X = a.X; k.k.ldx = a.ldx; k.k.Y = a.Y; k.k.ldy = a.ldy; k.k.Y2 = a.Y2; k.k.ldy2 = a.ldy2;
+  k.k.bias = a.bias; k.k.Zprev = a.Zprev; k.k.ldz = a.ldz; k.k.n_mask_rows = a.n_mask_rows;
+  k.k.d = a.d; k.k.epilogue = a.epilogue; k.k.row_bytes = (uint32_t)(a.ldx * (int64_t)es);
+  k.ent = P->ent; k.wb = P->wb; k.nfull = P->nfull; k.obase = P->obase;
+  k.panel_row0 = P->panel_row0; k.row_v = P->row_v; k.vlds = P->vlds; k.order = P->order;
+  k.ctr = P->ctr; k.n_panels = P->n_panels; k.ns = ns;
+  k.wg_per_list = std::max(1, n_wg / kPanelLists);
+  const int64_t units = (int64_t)ns * P->n_panels;
+  if (kPanelLists % ns == 0) {
+    k.q = kPanelLists / ns;
+    for (int i = 0; i < kPanelLists; ++i) {
+      const int aoff = i % k.q;
+      k.list_begin[i] = 0;
+      k.list_len[i] = P->n_panels > aoff ? (int)ceil_div(P->n_panels - aoff, k.q) : 0;
+    }
+  } else {
+    k.q = 0;
+    for (int i = 0; i < kPanelLists; ++i) {
+      const int64_t b = units * i / kPanelLists, e = units * (i + 1) / kPanelLists;
+      k.list_begin[i] = (int)b; k.list_len[i] = (int)(e - b);
+    }
+  }
+  const size_t lds = (size_t)((P->nv_max * sw + 3) & ~3) * sizeof(float);
+
+  const double csr = 8.0 * (double)a.nnz + 8.0 * (double)(a.n_rows + 1), fe = (double)es * a.d;
+  ProfScope ps(a.transposed ? GCN_K_SPMM_T : GCN_K_SPMM, s, a.d, a.dtype, a.n_rows, a.nnz,
+               csr + fe * (double)(a.n_cols + a.n_rows), csr + fe * (double)(a.nnz + a.n_rows), 2.0 * (double)a.nnz * a.d);
+  k_panel_reset<<<1, 64, 0, s>>>(P->ctr);
+  int rc;
+  if (a.dtype == GCN_BF16) rc = sw == 32 ? launch_panel<bf16_t, 8, 4>(k, n_wg, lds, s) : launch_panel<bf16_t, 8, 2>(k, n_wg, lds, s);
+  else rc = sw == 32 ? launch_panel<float, 4, 8>(k, n_wg, lds, s) : launch_panel<float, 4, 4>(k, n_wg, lds, s);
+  GCN_TRY(rc);
+  *used = true;
+  return GCN_OK;
+}
+
+}  // namespace gcn
