@@ -185,12 +185,17 @@ __device__ __forceinline__ void consume_batch(const uint32_t (&e)[2 * (8 / LPG)]
       for (int v = 0; v < V; ++v) av[v] = 0.f;
       cur = lid;
     }
-    const T* xe = reinterpret_cast<const T*>(&x[i]);
+    float xf[V];
+    if constexpr (sizeof(T) == 4) {
+      xf[0] = x[i].x; xf[1] = x[i].y; xf[2] = x[i].z; xf[3] = x[i].w;
+    } else {                       // two bf16 per 32-bit word, the lower-indexed one in the low half
+      const uint32_t wd[4] = {x[i].x, x[i].y, x[i].z, x[i].w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { xf[2 * k] = __uint_as_float(wd[k] << 16); xf[2 * k + 1] = __uint_as_float(wd[k] & 0xffff0000u); }
+    }
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-      float xv;
-      if constexpr (sizeof(T) == 4) xv = (float)xe[v]; else xv = bf16_to_f32((bf16_t)xe[v]);
-      if (CHECK) xv = valid ? xv : 0.f;
+      const float xv = CHECK ? (valid ? xf[v] : 0.f) : xf[v];
       av[v] = fmaf(CHECK ? (valid ? w : 0.f) : w, xv, av[v]);
     }
   }
@@ -300,16 +305,29 @@ __global__ __launch_bounds__(kPanelThreads) void k_spmm_panel(PanelK a) {
     __syncthreads();
     if (tid == 0) __hip_atomic_fetch_add(a.ctr + kPanelLists + from, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-    // ---- write the panel: add the parts of each row in order, apply the epilogue
-    const int n_el = (row1 - row0) * SW;
-    for (int i = tid; i < n_el; i += kPanelThreads) {
-      const int r = row0 + i / SW, f = i % SW;
+    // ---- write the panel: add the parts of each row in order, apply the epilogue.  A wavefront takes
+    // 64 rows at a time: lane i fetches the description of row i, then the lanes walk the rows
+    // 64 / SW at a step, SW features each, so the global loads are not on the path of every element.
+    {
+      constexpr int RPS = 64 / SW;                      // rows per step
+      const int f = lane % SW;
       const int c = slice * 32 + f;
-      if (c < a.k.d) {
-        const int v0 = a.row_v[r], v1 = a.row_v[r + 1];
-        float sum = 0.f;
-        for (int vg = v0; vg < v1; ++vg) sum += acc[a.vlds[vg] * SW + f];
-        finish_element<T>(a.k, r, c, sum);
+      for (int rb = row0 + w * 64; rb < row1; rb += kPanelWaves * 64) {
+        const int mine = rb + lane < row1 ? rb + lane : row1 - 1;
+        const int v0 = a.row_v[mine], v1 = a.row_v[mine + 1];
+        const int first = a.vlds[v0];
+        const int n_here = row1 - rb < 64 ? row1 - rb : 64;
+        for (int j = 0; j < n_here; j += RPS) {
+          const int rr = j + lane / SW;
+          const int src = (rr < n_here ? rr : n_here - 1) << 2;
+          const int p0 = __builtin_amdgcn_ds_bpermute(src, v0), p1 = __builtin_amdgcn_ds_bpermute(src, v1);
+          const int l0 = __builtin_amdgcn_ds_bpermute(src, first);
+          if (rr < n_here && c < a.k.d) {
+            float sum = acc[l0 * SW + f];
+            for (int vg = p0 + 1; vg < p1; ++vg) sum += acc[a.vlds[vg] * SW + f];
+            finish_element<T>(a.k, rb + rr, c, sum);
+          }
+        }
       }
     }
     __syncthreads();
