@@ -92,7 +92,8 @@ struct Schedule {
 // 64 / lpg lane groups; every lane group owns some virtual rows of the panel (dealt out so that all
 // groups get about the same number of entries) and reads its own stream of entries, sorted by
 // (column block, virtual row, column).  The streams of the groups of one wavefront are stored
-// interleaved in batches of 8 entries per group, padded with kNoEntry where a stream has ended.
+// interleaved in batches of 8 entries per group (32 for half-wavefront groups), padded with kNoEntry
+// where a stream has ended.
 constexpr int kPanelWaves = 16;
 constexpr int kPanelLists = 8;      // one work list per XCD
 struct PanelPlan {
@@ -105,9 +106,11 @@ struct PanelPlan {
   int nv_max = 0;          // most virtual rows in one panel
   int n_panels = 0;
   int64_t n_rows = 0, total_vrows = 0, n_batches = 0;
-  uint2* ent = nullptr;           // [n_batches * 8 * (64 / lpg)] {index in owner << 24 | column, value bits}
+  uint2* ent = nullptr;           // [n_batches * epb * (64 / lpg)] {index in owner << 24 | column, value bits}; epb = 8, or 32 for lpg 32
   int64_t* wb = nullptr;          // [n_panels * kPanelWaves + 1] first batch of each wavefront
   int32_t* nfull = nullptr;       // [n_panels * kPanelWaves] leading batches without padding
+  int n_cb = 1;                   // column blocks
+  int32_t* cbend = nullptr;       // [n_panels * kPanelWaves * n_cb] batches of a wavefront up to the end of a column block
   int32_t* obase = nullptr;       // [n_panels * kPanelWaves * (64 / lpg)] first accumulator row of each group
   int32_t* panel_row0 = nullptr;  // [n_panels + 1] first row of each panel
   int32_t* row_v = nullptr;       // [n_rows + 1] index of the first virtual row of each row
@@ -213,6 +216,8 @@ int gemm_nn_direct(const void* A, int64_t lda, const float* W, int64_t ldw, void
 size_t gemm_tn_direct_ws_bytes(int64_t Kd, int M, int N);
 int gemm_tn_direct_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype,
                             float* partial, int* nsplit_out, hipStream_t s);
+// dst[rows x ld_dst] = src[rows x d] (leading dimension ld_src), zero in the padding columns
+int pad_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int d, int dtype, hipStream_t s);
 // Wt[N x K] = W[K x N]^T (f32, small)
 int transpose_f32(const float* W, int K, int N, float* Wt, hipStream_t s);
 // out[c] = sum_i G[i, c]  (deterministic), ws at least colsum_ws_bytes

@@ -102,9 +102,15 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
       void* T = ws.take((size_t)A->nc * ldt * es);
       const int64_t kd = AH_saved ? A->nr : A->nc;
       void* tn = ws.take(gemm_tn_ws_bytes(kd, d_in, d_out));
+      // rows of G whose pitch is not a multiple of 16 bytes are first copied to a padded buffer: the
+      // sparse product then gathers with vector loads
+      const bool pad_g = ldt != d_out;
+      void* Gp = pad_g ? ws.take((size_t)A->nr * ldt * es) : nullptr;
       if (pass) {
-        SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, G, d_out, T, ldt, nullptr, 0,
-                    d_out, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+        if (pad_g) GCN_TRY(pad_rows(G, d_out, Gp, ldt, A->nr, d_out, dtype, s));
+        SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, pad_g ? Gp : G,
+                    pad_g ? ldt : (int64_t)d_out, T, ldt, nullptr, 0, d_out, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+        sp.x_rows_padded = pad_g;
         sp.owner = Am;
         GCN_TRY(spmm_launch(sp, hub, s));
         if (dH) {

@@ -164,6 +164,27 @@ static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* 
   return GCN_OK;
 }
 
+// dst[r][0 .. ld_dst) = src[r][0 .. d) followed by zeros: a copy with a padded leading dimension
+__global__ __launch_bounds__(256) void k_pad_rows(const char* __restrict__ src, int64_t ld_src, char* __restrict__ dst,
+                                                  int64_t ld_dst, int64_t rows, int d, int es) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * ld_dst) return;
+  const int64_t r = i / ld_dst; const int c = (int)(i % ld_dst);
+  if (es == 4) reinterpret_cast<uint32_t*>(dst)[i] = c < d ? reinterpret_cast<const uint32_t*>(src)[r * ld_src + c] : 0u;
+  else reinterpret_cast<uint16_t*>(dst)[i] = c < d ? reinterpret_cast<const uint16_t*>(src)[r * ld_src + c] : (uint16_t)0;
+}
+
+int pad_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int d, int dtype, hipStream_t s) {
+  if (rows <= 0) return GCN_OK;
+  const int es = dtype == GCN_BF16 ? 2 : 4;
+  const int64_t n = rows * ld_dst;
+  const double by = (double)es * (double)rows * (double)(d + ld_dst);
+  ProfScope ps(GCN_K_OTHER, s, d, dtype, rows, 0, by, by, 0.0);
+  k_pad_rows<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>((const char*)src, ld_src, (char*)dst, ld_dst, rows, d, es);
+  GCN_CHECK_LAUNCH();
+  return GCN_OK;
+}
+
 }  // namespace gcn
 
 using namespace gcn;

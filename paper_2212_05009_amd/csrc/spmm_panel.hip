@@ -20,6 +20,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <cmath>
 #include <new>
 #include <queue>
 #include <utility>
@@ -44,10 +45,11 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct PanelK {
   SpmmK k;                       // X, Y and epilogue fields
-  const uint2* ent; const int64_t* wb; const int32_t* nfull; const int32_t* obase;
+  const uint2* ent; const int64_t* wb; const int32_t* nfull; const int32_t* cbend; const int32_t* obase;
   const int32_t* panel_row0; const int32_t* row_v; const int32_t* vlds; const int32_t* order;
   uint32_t* ctr;                 // [0, kPanelLists): next unit of each list; [kPanelLists, 2 kPanelLists): units done
-  int n_panels, ns;
+  int n_panels, ns, n_cb;
+  int soft_sync;                 // 0: no column-block barriers (experiments)
   int q;                         // > 0: q lists share a slice (list = slice * q + a takes panels a, a + q, ...)
   int list_begin[kPanelLists];   // q == 0: list i holds the units [list_begin[i], list_begin[i] + list_len[i]) of the
   int list_len[kPanelLists];     //         slice-major enumeration unit = slice * n_panels + position
@@ -80,8 +82,9 @@ __global__ void k_plan_keys(const int64_t* __restrict__ ptr, int64_t n_rows, int
   pay[p] = (uint32_t)p;
 }
 
-// batches of each wavefront: enough for its longest group stream; nfull = batches every group fills
-__global__ void k_plan_waves(const int64_t* __restrict__ oseg, int64_t n_waves, int groups,
+// batches of each wavefront: enough for its longest group stream; nfull = batches every group fills.
+// epb = entries per group and batch.
+__global__ void k_plan_waves(const int64_t* __restrict__ oseg, int64_t n_waves, int groups, int epb,
                              uint32_t* __restrict__ nb, int32_t* __restrict__ nfull) {
   const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (w >= n_waves) return;
@@ -90,8 +93,24 @@ __global__ void k_plan_waves(const int64_t* __restrict__ oseg, int64_t n_waves, 
     const int64_t len = oseg[w * groups + g + 1] - oseg[w * groups + g];
     mx = len > mx ? len : mx; mn = len < mn ? len : mn;
   }
-  nb[w] = (uint32_t)((mx + 7) / 8);
-  nfull[w] = (int32_t)(mn / 8);
+  nb[w] = (uint32_t)((mx + epb - 1) / epb);
+  nfull[w] = (int32_t)(mn / epb);
+}
+
+// cbend[w * n_cb + cb] = batches of wavefront w after which all of its groups are past column block cb
+// (seg[] = boundaries of the (owner, column block) runs of the sorted entries, id = owner << cbbits | cb)
+__global__ void k_plan_cbend(const int64_t* __restrict__ seg, int64_t n_waves, int groups, int epb, int n_cb, int cbbits,
+                             int32_t* __restrict__ cbend) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_waves * n_cb) return;
+  const int64_t w = i / n_cb; const int cb = (int)(i % n_cb);
+  int64_t mx = 0;
+  for (int g = 0; g < groups; ++g) {
+    const int64_t o = w * groups + g;
+    const int64_t upto = seg[(o << cbbits) + cb + 1] - seg[o << cbbits];
+    mx = upto > mx ? upto : mx;
+  }
+  cbend[i] = (int32_t)((mx + epb - 1) / epb);
 }
 
 __global__ void k_plan_fill_pad(uint2* __restrict__ ent, int64_t n) {
@@ -101,7 +120,7 @@ __global__ void k_plan_fill_pad(uint2* __restrict__ ent, int64_t n) {
 
 __global__ void k_plan_scatter(const uint64_t* __restrict__ keys, const uint32_t* __restrict__ pay,
                                const int32_t* __restrict__ idx, const float* __restrict__ val, int64_t nnz,
-                               int shift, int groups, const int64_t* __restrict__ oseg,
+                               int shift, int groups, int epb, const int64_t* __restrict__ oseg,
                                const int64_t* __restrict__ wb, uint2* __restrict__ ent) {
   const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (q >= nnz) return;
@@ -109,7 +128,7 @@ __global__ void k_plan_scatter(const uint64_t* __restrict__ keys, const uint32_t
   const int64_t o = (int64_t)(key >> shift);
   const int64_t k = q - oseg[o];
   const int64_t w = o / groups, g = o % groups;
-  const int64_t pos = (wb[w] + k / 8) * (8 * groups) + g * 8 + k % 8;
+  const int64_t pos = (wb[w] + k / epb) * ((int64_t)epb * groups) + g * epb + k % epb;
   const uint32_t p = pay[q];
   ent[pos] = make_uint2(((uint32_t)(key & 0xffu) << kColBits) | (uint32_t)idx[p], __float_as_uint(val[p]));
 }
@@ -201,13 +220,52 @@ __device__ __forceinline__ void consume_batch(const uint32_t (&e)[2 * (8 / LPG)]
   }
 }
 
+// Soft column-block barrier.  Left alone, the wavefronts of a workgroup drift several column blocks
+// apart (the instruction arbiter prefers the older ones) and the blocks in use no longer fit L2.  So
+// all wavefronts meet after every column block: wavefront w reaches the barrier of block cb when it
+// has done cbend[cb] batches.  Every wavefront passes exactly n_cb barriers per unit; where exactly it
+// passes them only changes speed, never results.
+struct SweepSync {
+  const int32_t* cbend;     // this wavefront's row of the table
+  int n_cb;
+  int k;                    // barriers passed so far
+  int next;                 // batches after which barrier k is due
+  int vals;                 // lane i: cbend[(k & ~63) + i]
+  int lane;
+  __device__ __forceinline__ void load_chunk() {     // only called with 0 <= k < n_cb
+    const int i = (k & ~63) + lane;
+    vals = cbend[i < n_cb ? i : n_cb - 1];
+  }
+  __device__ __forceinline__ void init(const int32_t* p, int n, int ln) {
+    cbend = p; n_cb = n > 0 ? n : 0; k = 0; lane = ln; vals = 0; next = 0;
+    if (n_cb > 0) {
+      load_chunk();
+      next = __shfl(vals, 0, 64);
+    }
+  }
+  // call with the number of batches done; wave-uniform
+  __device__ __forceinline__ void arrive(int done) {
+    while (k < n_cb && done >= next) {
+      __syncthreads();
+      ++k;
+      if (k < n_cb) {
+        if ((k & 63) == 0) load_chunk();
+        next = __shfl(vals, k & 63, 64);
+      }
+    }
+  }
+  __device__ __forceinline__ void finish() {
+    while (k < n_cb) { __syncthreads(); ++k; }
+  }
+};
+
 // batches [b0, b1) of one wavefront, two batches of gathers in flight.  Inside the loop there is no
 // conditional load between the gathers of a batch and their use, so the compiler's wait counts are
 // exact (the entries two batches ahead are always fetched, those of the last batch again at the end).
 template <typename T, int V, int LPG, bool CHECK>
-__device__ __forceinline__ void sweep(const uint2* __restrict__ ent, int64_t b0, int64_t b1, int lane, int g,
+__device__ __forceinline__ void sweep(const uint2* __restrict__ ent, int64_t wave_b0, int64_t b0, int64_t b1, int lane, int g,
                                       const char* xb, uint32_t row_bytes, uint32_t xoff, float* __restrict__ myacc,
-                                      bool active, int& cur, float (&av)[V]) {
+                                      bool active, int& cur, float (&av)[V], SweepSync& sync) {
   constexpr int EPL = 8 / LPG, G = 64 / LPG, BATCH = 8 * G;
   typedef typename Vec<T, V>::type XV;
   if (b0 >= b1) return;
@@ -219,6 +277,7 @@ __device__ __forceinline__ void sweep(const uint2* __restrict__ ent, int64_t b0,
   issue_batch<T, V, LPG, CHECK>(eA, g, xb, row_bytes, xoff, xA);
   int64_t b = b0;
   while (b + 2 <= last) {
+    sync.arrive((int)(b - wave_b0));
     // xA: gathers of batch b (entries eA) in flight; eB: entries of batch b + 1
     load_entries<EPL>(ent, b + 2, BATCH, lane, eC);
     issue_batch<T, V, LPG, CHECK>(eB, g, xb, row_bytes, xoff, xB);
@@ -236,11 +295,117 @@ __device__ __forceinline__ void sweep(const uint2* __restrict__ ent, int64_t b0,
   if (b < last) consume_batch<T, V, LPG, CHECK>(eB, g, xB, myacc, active, cur, av);
 }
 
+// ---- wide variant: a lane group is half a wavefront, 32 lanes x 4 fp32 = 128 features of a row ----
+// The two groups' entries of a batch sit in lanes [0, 32) and [32, 64) of the entry registers.  What
+// decides control flow (which accumulator row an entry belongs to) is read into scalar registers, so
+// the run bookkeeping costs no vector instructions and no divergence; per entry a lane does one
+// address multiply-add, one 16-byte gather and four multiply-adds.  Eight gathers per lane are kept
+// in flight in a ring that runs on across batch boundaries.
+constexpr int kWideDepth = 8;
+
+template <bool CHECK>
+__device__ __forceinline__ void sweep_wide(const uint2* __restrict__ ent, int64_t wave_b0, int64_t b0, int64_t b1, int lane,
+                                           const char* xb, uint32_t row_bytes, uint32_t xoff, float* __restrict__ myacc,
+                                           bool active, int (&cur)[2], float (&av)[4], SweepSync& sync) {
+  if (b0 >= b1) return;
+  const int half = lane >> 5;
+  const int64_t last = b1 - 1;
+  const u32x2* ep = reinterpret_cast<const u32x2*>(ent);
+  auto load_batch = [&](int64_t bq, uint32_t& pk, uint32_t& wt) {
+    const u32x2 t = __builtin_nontemporal_load(ep + (bq <= last ? bq : last) * 64 + lane);
+    pk = bq <= last ? t.x : kNoEntry; wt = bq <= last ? t.y : 0u;
+  };
+  auto gather = [&](uint32_t src_pk, int i, bool clamp) -> float4 {
+    uint32_t c = (uint32_t)__builtin_amdgcn_ds_bpermute((half * 32 + i) << 2, (int)src_pk);
+    if (clamp) c = c == kNoEntry ? 0u : c;         // padding gathers row 0 (a valid address) and is dropped later
+    return *reinterpret_cast<const float4*>(xb + (__umul24(c, row_bytes) + xoff));
+  };
+  uint32_t e_pk, e_w, n_pk, n_w;
+  load_batch(b0, e_pk, e_w);
+  load_batch(b0 + 1, n_pk, n_w);
+  float4 x[kWideDepth];
+#pragma unroll
+  for (int i = 0; i < kWideDepth; ++i) x[i] = gather(e_pk, i, CHECK);
+  for (int64_t b = b0; b < b1; ++b) {
+    sync.arrive((int)(b - wave_b0));
+    uint32_t nn_pk, nn_w;
+    load_batch(b + 2, nn_pk, nn_w);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      // ---- use entry i of both groups
+      const uint32_t s0 = (uint32_t)__builtin_amdgcn_readlane((int)e_pk, i);
+      const uint32_t s1 = (uint32_t)__builtin_amdgcn_readlane((int)e_pk, 32 + i);
+      float w = __int_as_float(__builtin_amdgcn_ds_bpermute((half * 32 + i) << 2, (int)e_w));
+      const bool ok0 = !CHECK || s0 != kNoEntry, ok1 = !CHECK || s1 != kNoEntry;
+      const int lid0 = (int)(s0 >> kColBits), lid1 = (int)(s1 >> kColBits);
+      if (ok0 && lid0 != cur[0]) {                                   // wave-uniform
+        if (cur[0] >= 0 && half == 0) {
+          if (active) add_to_row<4>(myacc + cur[0] * 128, av);
+          av[0] = av[1] = av[2] = av[3] = 0.f;
+        }
+        cur[0] = lid0;
+      }
+      if (ok1 && lid1 != cur[1]) {
+        if (cur[1] >= 0 && half == 1) {
+          if (active) add_to_row<4>(myacc + cur[1] * 128, av);
+          av[0] = av[1] = av[2] = av[3] = 0.f;
+        }
+        cur[1] = lid1;
+      }
+      float4 xv = x[i % kWideDepth];
+      if (CHECK) {
+        const bool ok = half ? ok1 : ok0;
+        w = ok ? w : 0.f;
+        xv.x = ok ? xv.x : 0.f; xv.y = ok ? xv.y : 0.f; xv.z = ok ? xv.z : 0.f; xv.w = ok ? xv.w : 0.f;
+      }
+      av[0] = fmaf(w, xv.x, av[0]); av[1] = fmaf(w, xv.y, av[1]); av[2] = fmaf(w, xv.z, av[2]); av[3] = fmaf(w, xv.w, av[3]);
+      // ---- put the gather of entry i + depth in flight (from the next batch near the end of this one)
+      const int j = i + kWideDepth;
+      if (j < 32) x[i % kWideDepth] = gather(e_pk, j, CHECK);
+      else x[i % kWideDepth] = gather(n_pk, j - 32, true);
+    }
+    e_pk = n_pk; e_w = n_w; n_pk = nn_pk; n_w = nn_w;
+  }
+}
+
+// common tail of a unit: add the parts of each row in order, apply the epilogue, write the rows.  A
+// wavefront takes 64 rows at a time: lane i fetches the description of row i, then the lanes walk
+// the rows, SW features of a row at a step (64 / SW rows per step when SW < 64).
+template <typename T, int SW>
+__device__ __forceinline__ void write_panel(const PanelK& a, const float* __restrict__ acc, int row0, int row1, int slice,
+                                            int w, int lane) {
+  constexpr int RPS = SW >= 64 ? 1 : 64 / SW;          // rows per step
+  constexpr int PASSES = SW >= 64 ? SW / 64 : 1;       // steps per row
+  for (int rb = row0 + w * 64; rb < row1; rb += kPanelWaves * 64) {
+    const int mine = rb + lane < row1 ? rb + lane : row1 - 1;
+    const int v0 = a.row_v[mine], v1 = a.row_v[mine + 1];
+    const int first = a.vlds[v0];
+    const int n_here = row1 - rb < 64 ? row1 - rb : 64;
+    for (int j = 0; j < n_here; j += RPS) {
+      const int rr = j + (SW >= 64 ? 0 : lane / SW);
+      const int src = (rr < n_here ? rr : n_here - 1) << 2;
+      const int p0 = __builtin_amdgcn_ds_bpermute(src, v0), p1 = __builtin_amdgcn_ds_bpermute(src, v1);
+      const int l0 = __builtin_amdgcn_ds_bpermute(src, first);
+#pragma unroll
+      for (int ps = 0; ps < PASSES; ++ps) {
+        const int f = SW >= 64 ? lane + 64 * ps : lane % SW;
+        const int c = slice * SW + f;
+        if (rr < n_here && c < a.k.d) {
+          float sum = acc[l0 * SW + f];
+          for (int vg = p0 + 1; vg < p1; ++vg) sum += acc[a.vlds[vg] * SW + f];
+          finish_element<T>(a.k, rb + rr, c, sum);
+        }
+      }
+    }
+  }
+}
+
 template <typename T, int V, int LPG>
 __global__ __launch_bounds__(kPanelThreads) void k_spmm_panel(PanelK a) {
   constexpr int G = 64 / LPG;
-  constexpr int SW = V * LPG;
-  static_assert(G * LPG == 64 && 8 % LPG == 0 && V % 4 == 0, "lane groups must tile the wavefront");
+  constexpr int SW = V * LPG;                // features of a slice = accumulator floats per virtual row
+  static_assert(G * LPG == 64 && (LPG == 32 || 8 % LPG == 0) && V % 4 == 0, "lane groups must tile the wavefront");
+  static_assert(LPG != 32 || (V == 4 && sizeof(T) == 4), "the half-wavefront variant is fp32 only");
   extern __shared__ __align__(16) float acc[];
   __shared__ int s_unit[2];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -289,47 +454,33 @@ __global__ __launch_bounds__(kPanelThreads) void k_spmm_panel(PanelK a) {
       const int64_t gw = (int64_t)panel * kPanelWaves + w;
       const int64_t bb = a.wb[gw], be = a.wb[gw + 1];
       const int64_t bf = bb + a.nfull[gw];
-      const int c0 = slice * 32 + l * V;
+      const int c0 = slice * SW + l * V;
       const bool active = c0 < a.k.d;
-      const uint32_t xoff = (uint32_t)((active ? c0 : slice * 32) * (int)sizeof(T));
+      const uint32_t xoff = (uint32_t)((active ? c0 : slice * SW) * (int)sizeof(T));
       const char* xb = reinterpret_cast<const char*>(a.k.X);
       float* myacc = acc + a.obase[gw * G + g] * SW + l * V;
-      int cur = -1;
+      SweepSync sync;
+      sync.init(a.cbend + gw * a.n_cb, a.soft_sync ? a.n_cb : 0, lane);
       float av[V];
 #pragma unroll
       for (int v = 0; v < V; ++v) av[v] = 0.f;
-      sweep<T, V, LPG, false>(a.ent, bb, bf, lane, g, xb, a.k.row_bytes, xoff, myacc, active, cur, av);
-      sweep<T, V, LPG, true>(a.ent, bf, be, lane, g, xb, a.k.row_bytes, xoff, myacc, active, cur, av);
-      if (cur >= 0 && active) add_to_row<V>(myacc + cur * SW, av);
+      if constexpr (LPG == 32) {
+        int cur[2] = {-1, -1};
+        sweep_wide<false>(a.ent, bb, bb, bf, lane, xb, a.k.row_bytes, xoff, myacc, active, cur, av, sync);
+        sweep_wide<true>(a.ent, bb, bf, be, lane, xb, a.k.row_bytes, xoff, myacc, active, cur, av, sync);
+        const int mycur = g ? cur[1] : cur[0];
+        if (mycur >= 0 && active) add_to_row<4>(myacc + mycur * SW, av);
+      } else {
+        int cur = -1;
+        sweep<T, V, LPG, false>(a.ent, bb, bb, bf, lane, g, xb, a.k.row_bytes, xoff, myacc, active, cur, av, sync);
+        sweep<T, V, LPG, true>(a.ent, bb, bf, be, lane, g, xb, a.k.row_bytes, xoff, myacc, active, cur, av, sync);
+        if (cur >= 0 && active) add_to_row<V>(myacc + cur * SW, av);
+      }
+      sync.finish();
     }
     __syncthreads();
     if (tid == 0) __hip_atomic_fetch_add(a.ctr + kPanelLists + from, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-
-    // ---- write the panel: add the parts of each row in order, apply the epilogue.  A wavefront takes
-    // 64 rows at a time: lane i fetches the description of row i, then the lanes walk the rows
-    // 64 / SW at a step, SW features each, so the global loads are not on the path of every element.
-    {
-      constexpr int RPS = 64 / SW;                      // rows per step
-      const int f = lane % SW;
-      const int c = slice * 32 + f;
-      for (int rb = row0 + w * 64; rb < row1; rb += kPanelWaves * 64) {
-        const int mine = rb + lane < row1 ? rb + lane : row1 - 1;
-        const int v0 = a.row_v[mine], v1 = a.row_v[mine + 1];
-        const int first = a.vlds[v0];
-        const int n_here = row1 - rb < 64 ? row1 - rb : 64;
-        for (int j = 0; j < n_here; j += RPS) {
-          const int rr = j + lane / SW;
-          const int src = (rr < n_here ? rr : n_here - 1) << 2;
-          const int p0 = __builtin_amdgcn_ds_bpermute(src, v0), p1 = __builtin_amdgcn_ds_bpermute(src, v1);
-          const int l0 = __builtin_amdgcn_ds_bpermute(src, first);
-          if (rr < n_here && c < a.k.d) {
-            float sum = acc[l0 * SW + f];
-            for (int vg = p0 + 1; vg < p1; ++vg) sum += acc[a.vlds[vg] * SW + f];
-            finish_element<T>(a.k, rb + rr, c, sum);
-          }
-        }
-      }
-    }
+    write_panel<T, SW>(a, acc, row0, row1, slice, w, lane);
     __syncthreads();
   }
 }
@@ -360,7 +511,7 @@ int device_cus() {
 
 void free_plan(PanelPlan* p) {
   if (!p) return;
-  void* ptrs[] = {p->ent, p->wb, p->nfull, p->obase, p->panel_row0, p->row_v, p->vlds, p->order, p->ctr};
+  void* ptrs[] = {p->ent, p->wb, p->nfull, p->cbend, p->obase, p->panel_row0, p->row_v, p->vlds, p->order, p->ctr};
   for (void* q : ptrs) if (q) (void)hipFree(q);
   delete p;
 }
@@ -379,6 +530,7 @@ int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shif
   const int64_t n_cols = transposed ? A->nr : A->nc;
   const int n_wg = device_cus();
   const int groups = 64 / lpg;
+  const int epb = lpg >= 32 ? 32 : 8;              // entries per group and batch
   const int n_own = kPanelWaves * groups;          // owners (lane groups) per panel
 
   std::vector<int64_t> ptr((size_t)n + 1);
@@ -391,6 +543,11 @@ int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shif
   for (int64_t r = 0; r < n; ++r) max_len = std::max(max_len, ptr[r + 1] - ptr[r]);
   // a part should be well below a lane group's share of a panel, or the groups cannot be balanced
   int part_len = nnz / std::max<int64_t>(n, 1) < 128 ? 256 : 512;
+  if (lpg >= 32) {       // few lane groups per panel: parts of about a quarter of a group's share
+    const double share = (double)nnz / (double)std::max<int64_t>(n, 1) * cap / n_own / 4.0;
+    part_len = 32;
+    while (part_len < 512 && part_len * 2 <= share) part_len *= 2;
+  }
   int nv = cap;
   int64_t total_v = 0;
   for (;;) {
@@ -489,19 +646,26 @@ int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shif
   const int64_t n_waves = (int64_t)n_panels * kPanelWaves, n_owners = (int64_t)n_panels * n_own;
   GCN_TRY(dev_alloc((void**)&P->wb, sizeof(int64_t) * ((size_t)n_waves + 1)));
   GCN_TRY(dev_alloc((void**)&P->nfull, sizeof(int32_t) * (size_t)n_waves));
+  const int n_cb = (int)ceil_div(n_cols, (int64_t)1 << cb_shift);
+  const int cbbits = bits_for_count(n_cb);
+  const int64_t n_seg = n_owners << cbbits;
+  if (n_seg > (1LL << 26) || n_waves * n_cb > (1LL << 26)) return GCN_OK;     // too many column blocks for this layout
+  P->n_cb = n_cb;
+  GCN_TRY(dev_alloc((void**)&P->cbend, sizeof(int32_t) * (size_t)(n_waves * n_cb)));
   GCN_TRY(dev_alloc((void**)&P->obase, sizeof(int32_t) * (size_t)n_owners));
   GCN_TRY(dev_alloc((void**)&P->panel_row0, sizeof(int32_t) * ((size_t)n_panels + 1)));
   GCN_TRY(dev_alloc((void**)&P->row_v, sizeof(int32_t) * ((size_t)n + 1)));
   GCN_TRY(dev_alloc((void**)&P->vlds, sizeof(int32_t) * (size_t)total_v));
   GCN_TRY(dev_alloc((void**)&P->order, sizeof(int32_t) * (size_t)n_panels));
   GCN_TRY(dev_alloc((void**)&P->ctr, sizeof(uint32_t) * 2 * kPanelLists));
-  DevBuf d_vinfo, keys_a, keys_b, pay_a, pay_b, tmp, oseg, nb;
+  DevBuf d_vinfo, keys_a, keys_b, pay_a, pay_b, tmp, oseg, nb, seg;
   GCN_TRY(d_vinfo.alloc(sizeof(uint32_t) * (size_t)total_v));
   GCN_TRY(keys_a.alloc(sizeof(uint64_t) * (size_t)nnz));
   GCN_TRY(keys_b.alloc(sizeof(uint64_t) * (size_t)nnz));
   GCN_TRY(pay_a.alloc(sizeof(uint32_t) * (size_t)nnz));
   GCN_TRY(pay_b.alloc(sizeof(uint32_t) * (size_t)nnz));
   GCN_TRY(oseg.alloc(sizeof(int64_t) * ((size_t)n_owners + 1)));
+  GCN_TRY(seg.alloc(sizeof(int64_t) * ((size_t)n_seg + 1)));
   GCN_TRY(nb.alloc(sizeof(uint32_t) * (size_t)n_waves));
   size_t tb = sort_tmp_bytes(nnz);
   if (scan_tmp_bytes(n_waves) > tb) tb = scan_tmp_bytes(n_waves);
@@ -512,7 +676,6 @@ int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shif
   GCN_HIP(hipMemcpyAsync(P->vlds, vlds.data(), sizeof(int32_t) * (size_t)total_v, hipMemcpyHostToDevice, s));
   GCN_HIP(hipMemcpyAsync(P->obase, obase.data(), sizeof(int32_t) * (size_t)n_owners, hipMemcpyHostToDevice, s));
   GCN_HIP(hipMemcpyAsync(d_vinfo.p, vinfo.data(), sizeof(uint32_t) * (size_t)total_v, hipMemcpyHostToDevice, s));
-  const int cbbits = bits_for_count(ceil_div(n_cols, (int64_t)1 << cb_shift));
   const int ownbits = bits_for_count(n_owners);
   if (kLidBits + cbbits + ownbits > 64) return GCN_OK;
   const unsigned grid = (unsigned)ceil_div(nnz, 256);
@@ -523,17 +686,19 @@ int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shif
   GCN_TRY(radix_sort_u64(keys_a.as<uint64_t>(), keys_b.as<uint64_t>(), pay_a.as<uint32_t>(), pay_b.as<uint32_t>(), nnz, 0,
                          kLidBits + cbbits + ownbits, tmp.p, s, &sorted, &spay));
   GCN_TRY(segment_boundaries(sorted, nnz, kLidBits + cbbits, n_owners, oseg.as<int64_t>(), s));
-  k_plan_waves<<<(unsigned)ceil_div(n_waves, 256), 256, 0, s>>>(oseg.as<int64_t>(), n_waves, groups, nb.as<uint32_t>(), P->nfull);
+  GCN_TRY(segment_boundaries(sorted, nnz, kLidBits, n_seg, seg.as<int64_t>(), s));
+  k_plan_waves<<<(unsigned)ceil_div(n_waves, 256), 256, 0, s>>>(oseg.as<int64_t>(), n_waves, groups, epb, nb.as<uint32_t>(), P->nfull);
+  k_plan_cbend<<<(unsigned)ceil_div(n_waves * n_cb, 256), 256, 0, s>>>(seg.as<int64_t>(), n_waves, groups, epb, n_cb, cbbits, P->cbend);
   GCN_CHECK_LAUNCH();
   GCN_TRY(exclusive_scan_u32(nb.as<uint32_t>(), P->wb, n_waves, tmp.p, s));
   int64_t n_batches = 0;
   GCN_HIP(hipMemcpyAsync(&n_batches, P->wb + n_waves, sizeof(int64_t), hipMemcpyDeviceToHost, s));
   GCN_HIP(hipStreamSynchronize(s));
   P->n_batches = n_batches;
-  const int64_t n_ent = n_batches * 8 * groups;
+  const int64_t n_ent = n_batches * epb * groups;
   GCN_TRY(dev_alloc((void**)&P->ent, sizeof(uint2) * (size_t)n_ent));
   if (n_ent > 0) k_plan_fill_pad<<<(unsigned)ceil_div(n_ent, 256), 256, 0, s>>>(P->ent, n_ent);
-  k_plan_scatter<<<grid, 256, 0, s>>>(sorted, spay, d_idx, d_val, nnz, kLidBits + cbbits, groups, oseg.as<int64_t>(), P->wb, P->ent);
+  k_plan_scatter<<<grid, 256, 0, s>>>(sorted, spay, d_idx, d_val, nnz, kLidBits + cbbits, groups, epb, oseg.as<int64_t>(), P->wb, P->ent);
   GCN_CHECK_LAUNCH();
   GCN_HIP(hipStreamSynchronize(s));      // host vectors and temporaries go out of scope
   if (getenv("GCN_PANEL_VERBOSE"))
@@ -566,23 +731,33 @@ int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used) {
   auto aligned = [](const void* p, size_t al) { return ((uintptr_t)p % al) == 0; };
   const int V = a.dtype == GCN_BF16 ? 8 : 4;
   if (!((a.ldx % V) == 0 && aligned(a.X, 16) && ((a.d % V) == 0 || a.x_rows_padded))) return GCN_OK;
-  const int sw = a.d <= 16 ? 16 : 32;
+  // lane-group shape: half a wavefront per row (128 fp32 features) for wide fp32 products, else 32
+  // features per group (16 for products no wider than that)
+  const bool wide = a.dtype == GCN_F32 && a.d >= 64 && !getenv("GCN_PANEL_NARROW");
+  const int sw = wide ? 128 : a.d <= 16 ? 16 : 32;
   const int lpg = sw / V;
-  const int ns = sw == 16 ? 1 : (int)ceil_div(a.d, 32);
+  const int ns = (int)ceil_div(a.d, sw);
   // bytes of L2 one row of the operand occupies in an XCD that works on one slice
-  const double foot = ns == 1 ? (double)a.d * (double)es : 128.0;
+  const double foot = ns == 1 ? (double)a.d * (double)es : std::max(128.0, (double)sw * (double)es);
   int cb_shift = 10;
   while (cb_shift < 20 && (double)(2LL << cb_shift) * foot <= 2.0 * 1024 * 1024) ++cb_shift;
   const int n_wg = device_cus();
   if (force != 1) {
-    // Worth it when the gathers of one round re-read the operand many times and the operand does not
-    // sit in L2 anyway.  Measured (fp32, width 128): 1.7x faster than the row-per-wavefront kernel at
-    // reuse 80 (233 k rows, 490 entries per row), 1.2x slower at reuse 6 (262 k rows, 45 per row),
-    // where the longer instruction stream per entry costs more than the saved L2 misses.  The bf16
-    // instances need more registers than a 16-wave workgroup leaves them: row-per-wavefront for now.
+    // Worth it when (1) the operand is large enough to spill L2 and the gathers of one round re-read it
+    // several times, and (2) a virtual row has several entries per column block, so that most entries
+    // extend a run in registers instead of starting a new read-add-write of an accumulator row.
+    // Measured, fp32, 233 k rows with 490 entries each (runs of 8.6 / 32 entries): width 128, half-wavefront
+    // groups 3.2 ms, 8-lane groups 4.1 ms, row-per-wavefront kernel 7.3 ms; width 41: 2.6 against 3.4 ms.
+    // 262 k rows with 45 entries each (runs of 0.7 / 2.8): 1.17 ms and 0.56 ms against 0.48 ms.  The bf16
+    // instances do not beat the row-per-wavefront kernel (they are bound by instruction issue, not bytes).
     const int cap = std::min(kMaxVrows, kLdsBudget / (sw * 4));
-    const double reuse = (double)(n_wg / kPanelLists) * cap * ((double)a.nnz / (double)a.n_rows) / (double)a.n_cols;
-    if (a.dtype != GCN_F32 || a.nnz < (1 << 20) || (double)a.n_cols * foot < 6.0 * 1024 * 1024 || reuse < 20.0) return GCN_OK;
+    const double avg = (double)a.nnz / (double)a.n_rows;
+    const double reuse = (double)(n_wg / kPanelLists) * cap * avg / (double)a.n_cols;
+    const double n_cb = std::ceil((double)a.n_cols / (double)(1LL << cb_shift));
+    const double run = std::min(avg, 512.0) / n_cb;
+    if (a.dtype != GCN_F32 || a.nnz < (1 << 20) || (double)a.n_cols * foot < 6.0 * 1024 * 1024 || reuse < 3.0 ||
+        run < (wide ? 3.0 : 8.0))
+      return GCN_OK;
   }
 
   PanelPlan* P = nullptr;
@@ -598,9 +773,10 @@ int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used) {
   k.k.X = a.X; k.k.ldx = a.ldx; k.k.Y = a.Y; k.k.ldy = a.ldy; k.k.Y2 = a.Y2; k.k.ldy2 = a.ldy2;
   k.k.bias = a.bias; k.k.Zprev = a.Zprev; k.k.ldz = a.ldz; k.k.n_mask_rows = a.n_mask_rows;
   k.k.d = a.d; k.k.epilogue = a.epilogue; k.k.row_bytes = (uint32_t)(a.ldx * (int64_t)es);
-  k.ent = P->ent; k.wb = P->wb; k.nfull = P->nfull; k.obase = P->obase;
+  k.ent = P->ent; k.wb = P->wb; k.nfull = P->nfull; k.cbend = P->cbend; k.obase = P->obase;
   k.panel_row0 = P->panel_row0; k.row_v = P->row_v; k.vlds = P->vlds; k.order = P->order;
-  k.ctr = P->ctr; k.n_panels = P->n_panels; k.ns = ns;
+  k.ctr = P->ctr; k.n_panels = P->n_panels; k.ns = ns; k.n_cb = P->n_cb;
+  k.soft_sync = getenv("GCN_PANEL_NOSYNC") ? 0 : 1;      // experiment switch
   k.wg_per_list = std::max(1, n_wg / kPanelLists);
   const int64_t units = (int64_t)ns * P->n_panels;
   if (kPanelLists % ns == 0) {
@@ -625,6 +801,7 @@ int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used) {
   k_panel_reset<<<1, 64, 0, s>>>(P->ctr);
   int rc;
   if (a.dtype == GCN_BF16) rc = sw == 32 ? launch_panel<bf16_t, 8, 4>(k, n_wg, lds, s) : launch_panel<bf16_t, 8, 2>(k, n_wg, lds, s);
+  else if (sw == 128) rc = launch_panel<float, 4, 32>(k, n_wg, lds, s);
   else rc = sw == 32 ? launch_panel<float, 4, 8>(k, n_wg, lds, s) : launch_panel<float, 4, 4>(k, n_wg, lds, s);
   GCN_TRY(rc);
   *used = true;
