@@ -72,7 +72,7 @@ static int gather_v(const char* table, int64_t ldb, int64_t nt, int n_vec, const
 // last layer): one group of LPR lanes per row.  The loss terms are added in fp64: per thread,
 // then per block in a fixed tree, then over the blocks in block order.
 // ------------------------------------------------------------------------------------------
-constexpr int kLossBlocks = 8192;
+constexpr int kLossBlocks = 2048;
 __device__ double g_loss_partial[kLossBlocks];
 
 template <typename T> __device__ __forceinline__ float ldf(const T* p) {
@@ -103,18 +103,30 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, i
       for (int c = l; c < C; c += LPR) stf<T>(go + c, 0.f);
       continue;
     }
-    float mx = -INFINITY;
-    for (int c = l; c < C; c += LPR) mx = fmaxf(mx, ldf<T>(z + c));
+    float mx = -INFINITY, se = 0.f;
+    if (C <= LPR) {                      // one element per lane: one load, one exponential, one store
+      const bool in = l < C;
+      const float zv = in ? ldf<T>(z + l) : -INFINITY;
+      mx = zv;
 #pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-    float se = 0.f;
-    for (int c = l; c < C; c += LPR) se += expf(ldf<T>(z + c) - mx);
+      for (int off = 1; off < LPR; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+      const float ev = in ? expf(zv - mx) : 0.f;
+      se = ev;
 #pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) se += __shfl_xor(se, off, 64);
-    const float inv = 1.0f / se;
-    for (int c = l; c < C; c += LPR) {
-      float p = expf(ldf<T>(z + c) - mx) * inv;
-      stf<T>(go + c, scale * (p - (c == label ? 1.f : 0.f)));
+      for (int off = 1; off < LPR; off <<= 1) se += __shfl_xor(se, off, 64);
+      if (in) stf<T>(go + l, scale * (ev * (1.0f / se) - (l == label ? 1.f : 0.f)));
+    } else {
+      for (int c = l; c < C; c += LPR) mx = fmaxf(mx, ldf<T>(z + c));
+#pragma unroll
+      for (int off = 1; off < LPR; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+      for (int c = l; c < C; c += LPR) se += expf(ldf<T>(z + c) - mx);
+#pragma unroll
+      for (int off = 1; off < LPR; off <<= 1) se += __shfl_xor(se, off, 64);
+      const float inv = 1.0f / se;
+      for (int c = l; c < C; c += LPR) {
+        float p = expf(ldf<T>(z + c) - mx) * inv;
+        stf<T>(go + c, scale * (p - (c == label ? 1.f : 0.f)));
+      }
     }
     if (l == 0) local += (double)(mx + logf(se)) - (double)ldf<T>(z + label);
   }
