@@ -25,8 +25,12 @@
  *    grows on demand and is reused by later calls).  Calls that use the same handle must not
  *    overlap in time.
  *  - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls only enqueue
- *    work; they do not synchronise, except gcn_csr_build (it must learn nnz and nh) and a
- *    call that has to grow the handle's workspace.
+ *    work; they do not synchronise, except gcn_csr_build (it must learn nnz and nh), a
+ *    call that has to grow the handle's workspace, and the first sparse product of a new
+ *    width class on a handle whose matrix qualifies for the column-sweep kernel: that call
+ *    builds an execution plan (a re-sorted copy of the matrix, 8 bytes per stored entry plus
+ *    padding, kept in the handle until gcn_csr_free), which allocates and waits for the
+ *    stream.  Later calls of that width class reuse the plan.
  *  - Indices are int32, row/column pointers int64, matrix values and all accumulators fp32.
  *    dtype selects the element type of *feature* buffers: GCN_F32, or GCN_BF16 (bf16 storage,
  *    fp32 accumulation, round-to-nearest-even on store).
