@@ -187,6 +187,13 @@ int gcn_softmax_xent(const void* Z, int64_t ldz, int64_t nr, int C, int dtype, c
                      float scale, float* loss, void* G, int64_t ldg, void* stream);
 
 /*
+ * Weight update of gradient descent (Sec. 3.1, last equation; last line of Algorithm 2):
+ *   W <- W - lr * dW,   elementwise on n fp32 values (W and dW: device, contiguous, may not overlap).
+ * One fused multiply-add per element.  Not part of the timed forward+backward epoch.
+ */
+int gcn_sgd_update(float* W, const float* dW, int64_t n, float lr, void* stream);
+
+/*
  * Per-kernel timing, for benchmarks (instrumentation; no part of the paper's method).
  * While enabled, every kernel launch of the library is bracketed by a pair of HIP events recorded
  * on the stream the kernel is launched on, and described by one record.  Records are kept in

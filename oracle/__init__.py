@@ -206,3 +206,36 @@ def gather(table, idx):
     if rc != 0:
         raise ValueError("oracle gather: index out of range")
     return out
+
+
+def sgd_update(W, dW, lr):
+    """Gradient-descent step W - lr * dW (Sec. 3.1, the weight update), fp64 arithmetic, returned as fp32."""
+    return (np.asarray(W, dtype=np.float64) - float(lr) * np.asarray(dW, dtype=np.float64)).astype(np.float32)
+
+
+def train(g: Graph, X, Ws, y, lr, epochs, scale=None):
+    """Full-batch training of an L-layer GCN (Algorithm 1 forward, Algorithm 2 backward and update, on one
+    block): ReLU on all layers but the last, softmax cross-entropy on the last pre-activation.  Every stored
+    array (layer outputs, gradients, weights) is rounded to fp32 between steps, as the arrays of an fp32
+    implementation are; all sums are fp64.  Returns (losses per epoch before the update, final weights)."""
+    Ws = [np.asarray(W, dtype=np.float32).copy() for W in Ws]
+    L = len(Ws)
+    scale = 1.0 / g.nr if scale is None else scale
+    assert g.nh == 0, "training loop needs a whole graph (halo rows come from other processors)"
+    losses = []
+    for _ in range(epochs):
+        H = [_f32(X)]
+        for k in range(L):
+            f = layer_fwd(g, H[k], Ws[k], act="none" if k == L - 1 else "relu")
+            H.append((f["Z"] if k == L - 1 else f["Hout"]).astype(np.float32))
+        loss, _, G = softmax_xent(H[L], y, scale)
+        losses.append(loss)
+        G = G.astype(np.float32)
+        dWs = [None] * L
+        for k in range(L - 1, -1, -1):
+            b = layer_bwd(g, H[k], Ws[k], G, Zprev=H[k][: g.nr] if k > 0 else None, want_dH=k > 0)
+            dWs[k] = b["dW"]
+            if k > 0:
+                G = b["dH"][: g.nr].astype(np.float32)
+        Ws = [sgd_update(Ws[k], dWs[k], lr) for k in range(L)]
+    return losses, Ws

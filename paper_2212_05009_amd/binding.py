@@ -52,6 +52,8 @@ def _load():
     lib.gcn_layer_fwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]
     lib.gcn_layer_bwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.gcn_softmax_xent.argtypes = [vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, C.c_float, vp, vp, C.c_int64, vp]
+    lib.gcn_sgd_update.argtypes = [vp, vp, C.c_int64, C.c_float, vp]
+    lib.gcn_sgd_update.restype = C.c_int
     lib.gcn_profile_enable.argtypes = [C.c_int]
     lib.gcn_profile_enable.restype = C.c_int
     lib.gcn_profile_count.argtypes = [i64p]
@@ -279,6 +281,14 @@ def gcn_softmax_xent(Z: torch.Tensor, y: torch.Tensor, scale: float, loss: torch
     _check(_lib.gcn_softmax_xent(_ptr(Z), ldz, Z.shape[0], Cn, _dtype_code(Z), _ptr(y), float(scale), _ptr(loss),
                                  _ptr(G), ldg, _stream()), "gcn_softmax_xent")
     return loss
+
+
+def gcn_sgd_update(W: torch.Tensor, dW: torch.Tensor, lr: float):
+    _dev(W, torch.float32, "W"); _dev(dW, torch.float32, "dW")
+    if W.shape != dW.shape or not W.is_contiguous() or not dW.is_contiguous():
+        raise TypeError("gcn_sgd_update: W and dW must be contiguous and of one shape")
+    _check(_lib.gcn_sgd_update(_ptr(W), _ptr(dW), W.numel(), float(lr), _stream()), "gcn_sgd_update")
+    return W
 
 
 def gcn_profile_enable(on: bool):

@@ -197,11 +197,30 @@ int pad_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t
   return GCN_OK;
 }
 
+__global__ __launch_bounds__(256) void k_sgd(float* __restrict__ W, const float* __restrict__ dW, int64_t n, float lr) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) W[i] = fmaf(-lr, dW[i], W[i]);
+}
+
 }  // namespace gcn
 
 using namespace gcn;
 
 extern "C" const char* gcn_last_error(void) { return g_err; }
+
+extern "C" int gcn_sgd_update(float* W, const float* dW, int64_t n, float lr, void* stream) {
+  clear_error();
+  if (n < 0) return fail(GCN_EINVAL, "gcn_sgd_update: negative size");
+  if (n == 0) return GCN_OK;
+  if (!W || !dW) return fail(GCN_EINVAL, "gcn_sgd_update: NULL pointer");
+  if (n > 0x7fffffffLL * 256) return fail(GCN_EINVAL, "gcn_sgd_update: too many elements");
+  hipStream_t s = (hipStream_t)stream;
+  const double by = 12.0 * (double)n;
+  ProfScope ps(GCN_K_OTHER, s, 1, GCN_F32, n, 0, by, by, 2.0 * (double)n);
+  k_sgd<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(W, dW, n, lr);
+  GCN_CHECK_LAUNCH();
+  return GCN_OK;
+}
 
 extern "C" int gcn_halo_gather(const void* table, int64_t ld, int64_t n_table_rows, int d, int dtype,
                                const int32_t* d_idx, int64_t n_idx, void* recv, int64_t ldr, void* stream) {

@@ -419,3 +419,44 @@ def test_gather_identity_and_round_trip():
     assert np.array_equal(oracle.gather(T, [3, 3, 49]), T[[3, 3, 49]])
     with pytest.raises(ValueError):
         oracle.gather(T, [50])
+
+
+# ---- weight update and training loop (Sec. 3.1 last equation; Algorithm 2's update line) ----------------
+def test_sgd_update_closed_form():
+    W = np.array([[1.0, -2.0], [0.5, 4.0]], np.float32); dW = np.array([[2.0, 2.0], [-1.0, 8.0]], np.float32)
+    assert np.array_equal(oracle.sgd_update(W, dW, 0.25), np.array([[0.5, -2.5], [0.75, 2.0]], np.float32))
+
+
+def test_one_layer_on_an_edgeless_graph_is_softmax_regression():
+    """No edges: A + I = I and every degree is 1, so A^ = I and a one-layer GCN is multinomial logistic
+    regression; one training step must equal the textbook update W - lr X^T (softmax(XW) - Y) / n."""
+    rng = np.random.default_rng(4)
+    n, d, c = 50, 6, 4
+    e = np.zeros(0, np.int32)
+    g = oracle.graph_build(e, e, n)
+    assert np.array_equal(g.col, np.arange(n)) and np.all(g.val == 1.0)
+    X = rng.standard_normal((n, d)).astype(np.float32); W = rng.standard_normal((d, c)).astype(np.float32)
+    y = rng.integers(0, c, n).astype(np.int32)
+    losses, (W1,) = oracle.train(g, X, [W], y, lr=0.3, epochs=1)
+    Z = X.astype(np.float64) @ W.astype(np.float64)
+    Z = Z.astype(np.float32).astype(np.float64)              # the stored pre-activation is fp32
+    P = np.exp(Z - Z.max(1, keepdims=True)); P /= P.sum(1, keepdims=True)
+    Y = np.eye(c)[y]
+    want_loss = -np.mean(np.log(P[np.arange(n), y]))
+    G = ((P - Y) / n).astype(np.float32).astype(np.float64)  # the stored gradient is fp32
+    want_W = (W.astype(np.float64) - 0.3 * (X.astype(np.float64).T @ G)).astype(np.float32)
+    assert abs(losses[0] - want_loss) <= 1e-12 * abs(want_loss)
+    assert np.array_equal(W1, want_W)
+
+
+def test_training_loss_falls_on_a_small_graph():
+    rng = np.random.default_rng(8)
+    n = 200
+    u = rng.integers(0, n, 800); v = rng.integers(0, n, 800)
+    g = oracle.graph_build(np.concatenate([u, v]), np.concatenate([v, u]), n)
+    X = rng.standard_normal((n, 12)).astype(np.float32)
+    Ws = [(rng.standard_normal((12, 8)) * 0.4).astype(np.float32), (rng.standard_normal((8, 3)) * 0.4).astype(np.float32)]
+    y = rng.integers(0, 3, n).astype(np.int32)
+    losses, _ = oracle.train(g, X, Ws, y, lr=0.5, epochs=25)
+    assert all(b < a for a, b in zip(losses, losses[1:])), losses
+    assert losses[-1] < losses[0] - 0.01          # labels are random: little can be learnt, but the loss must move
