@@ -230,6 +230,10 @@ typedef struct {
 } gcn_profile_rec;
 
 int gcn_profile_enable(int on);
+/* Restricts recording to launches whose kind k has bit k set in kind_mask (-1: all kinds) and, if d >= 0,
+ * whose feature width equals d.  Lets a benchmark time one kernel inside its timed region at the cost of two
+ * events per launch of that kernel only.  Stays in force until changed. */
+int gcn_profile_filter(int kind_mask, int d);
 /* number of records held; *dropped (may be NULL) = launches not recorded for lack of capacity */
 int64_t gcn_profile_count(int64_t* dropped);
 int gcn_profile_get(int64_t i, gcn_profile_rec* out);

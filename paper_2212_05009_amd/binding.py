@@ -56,6 +56,8 @@ def _load():
     lib.gcn_sgd_update.restype = C.c_int
     lib.gcn_profile_enable.argtypes = [C.c_int]
     lib.gcn_profile_enable.restype = C.c_int
+    lib.gcn_profile_filter.argtypes = [C.c_int, C.c_int]
+    lib.gcn_profile_filter.restype = C.c_int
     lib.gcn_profile_count.argtypes = [i64p]
     lib.gcn_profile_count.restype = C.c_int64
     lib.gcn_profile_get.argtypes = [C.c_int64, C.POINTER(ProfileRec)]
@@ -293,6 +295,12 @@ def gcn_sgd_update(W: torch.Tensor, dW: torch.Tensor, lr: float):
 
 def gcn_profile_enable(on: bool):
     _check(_lib.gcn_profile_enable(1 if on else 0), "gcn_profile_enable")
+
+
+def gcn_profile_filter(kinds=None, d: int = -1):
+    """Record only launches of the named kinds (None: all) and, if d >= 0, of that feature width."""
+    mask = -1 if kinds is None else sum(1 << KIND_NAMES.index(k) for k in kinds)
+    _check(_lib.gcn_profile_filter(mask, int(d)), "gcn_profile_filter")
 
 
 def gcn_profile_records():

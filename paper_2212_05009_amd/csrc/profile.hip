@@ -15,6 +15,8 @@ struct Slot {
   bool closed = false;
 };
 std::atomic<int> g_enabled{0};
+std::atomic<int> g_kind_mask{-1};   // bit k set: launches of kind k are recorded
+std::atomic<int> g_only_d{-1};      // >= 0: only launches of this feature width are recorded
 std::mutex g_mu;
 std::vector<Slot> g_slots;      // events are created once and reused by later recordings
 int64_t g_used = 0, g_dropped = 0;
@@ -24,6 +26,9 @@ ProfScope::ProfScope(int kind, hipStream_t s, int d, int dtype, int64_t rows, in
                      double touched_bytes, double flops)
     : s_(s) {
   if (!g_enabled.load(std::memory_order_relaxed)) return;
+  if (!((g_kind_mask.load(std::memory_order_relaxed) >> kind) & 1)) return;
+  const int only_d = g_only_d.load(std::memory_order_relaxed);
+  if (only_d >= 0 && d != only_d) return;
   std::lock_guard<std::mutex> lk(g_mu);
   if (g_used >= kCapacity) { ++g_dropped; return; }
   if ((int64_t)g_slots.size() <= g_used) {
@@ -55,6 +60,13 @@ extern "C" int gcn_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_mu);
   if (on) { g_used = 0; g_dropped = 0; }
   g_enabled.store(on ? 1 : 0, std::memory_order_relaxed);
+  return GCN_OK;
+}
+
+extern "C" int gcn_profile_filter(int kind_mask, int d) {
+  clear_error();
+  g_kind_mask.store(kind_mask, std::memory_order_relaxed);
+  g_only_d.store(d, std::memory_order_relaxed);
   return GCN_OK;
 }
 
