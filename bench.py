@@ -248,6 +248,17 @@ def main():
     else:
         roof = {"bound": "hbm", "achieved": dom["alg_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(dom["alg_GBps"] / HBM_PEAK_GBS, 4), "traffic": None}
+    # HBM-side bytes per launch of that kernel, from the rocprofv3 counter runs summarised under profiles/
+    # (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size): a line "bench-traffic: ..." there
+    traffic_file = os.path.join(ROOT, "profiles", f"epoch_{args.workload}_{args.dtype}.md")
+    if os.path.exists(traffic_file):
+        want = f"kernel={dom['kind']} d={dom['d']} "
+        for line in open(traffic_file):
+            if line.startswith("bench-traffic:") and want in line:
+                kv = dict(t.split("=") for t in line.split()[1:])
+                roof["traffic"] = float(kv["read_bytes"]) + float(kv["write_bytes"])
+                roof["traffic_GBps"] = round(roof["traffic"] / dom["avg_ms"] / 1e6, 2)
+                roof["traffic_source"] = os.path.relpath(traffic_file, ROOT)
     roof["kernel"] = f"{dom['kind']} d={dom['d']} rows={dom['rows']} inner={dom['inner']}"
     roof["avg_launch_ms"] = dom["avg_ms"]
     roof["launches_timed"] = round(dom["launches_per_step"] * args.steps)
