@@ -35,7 +35,7 @@ class Epoch:
     other processors would send) at the start of that layer, inside the timed epoch.
     """
 
-    def __init__(self, gcn, torch, A, X_owned, Ws, y, bf16, table=None):
+    def __init__(self, gcn, torch, A, X_owned, Ws, y, bf16, table=None, overlap=True):
         self.gcn, self.torch, self.A, self.Ws, self.y, self.table = gcn, torch, A, Ws, y, table
         dev = X_owned.device
         fdt = torch.bfloat16 if bf16 else torch.float32
@@ -59,21 +59,54 @@ class Epoch:
                    for k in range(self.L)]
         self.dW = [torch.empty_like(W) for W in Ws]
         self.loss = torch.zeros(1, device=dev)
+        # a block with halo rows runs Algorithm 1's overlap: the halo rows of a layer input arrive on a second
+        # stream while the product with the owned columns runs; the halo columns are added once they are there
+        self.overlap = bool(A.nh) and overlap
+        if self.overlap:
+            self.side = torch.cuda.Stream()
+            self.P = [None if self.AH[k] is not None else torch.empty(nc, dims[k + 1], dtype=fdt, device=dev)
+                      for k in range(self.L)]
 
     def run(self):
         g, A, L, nr = self.gcn, self.A, self.L, self.A.nr
         for k in range(L):
             last = k == L - 1
+            out = self.Zlast if last else self.H[k + 1][:nr]
+            act = g.ACT_NONE if last else g.ACT_RELU
+            if self.overlap:
+                self.forward_overlapped(k, out, act)
+                continue
             if A.nh:
                 g.gcn_halo_gather(self.table, self.halo_gid, self.H[k][nr:])
-            out = self.Zlast if last else self.H[k + 1][:nr]
-            g.gcn_layer_fwd(A, self.H[k], self.Ws[k], out, act=g.ACT_NONE if last else g.ACT_RELU,
-                            AH_save=self.AH[k])
+            g.gcn_layer_fwd(A, self.H[k], self.Ws[k], out, act=act, AH_save=self.AH[k])
         g.gcn_softmax_xent(self.Zlast, self.y, 1.0 / nr, self.loss, self.G[L - 1])
         for k in range(L - 1, -1, -1):
             g.gcn_layer_bwd(A, self.H[k], self.Ws[k], self.G[k], self.dW[k],
                             dH=self.D[k - 1] if k > 0 else None, Zprev=self.H[k][:nr] if k > 0 else None,
                             AH_saved=self.AH[k])
+
+
+    def forward_overlapped(self, k, out, act):
+        """Layer k forward with the halo fetch under way during the owned-column product (same sums as
+        gcn_layer_fwd: sparse product first where the input is the narrower side, dense product first else)."""
+        g, A, torch, nr = self.gcn, self.A, self.torch, self.A.nr
+        H, W = self.H[k], self.Ws[k]
+        main = torch.cuda.current_stream()
+        self.side.wait_stream(main)        # the rows being replaced were read by the previous epoch's backward pass
+        with torch.cuda.stream(self.side):
+            g.gcn_halo_gather(self.table, self.halo_gid, H[nr:])
+        if self.AH[k] is not None:
+            g.gcn_spmm_part(A, g.PART_LOCAL, H, self.AH[k])
+            main.wait_stream(self.side)
+            g.gcn_spmm_part(A, g.PART_HALO, H, self.AH[k])
+            g.gcn_dense_fwd(self.AH[k], W, out, act=act)
+        else:
+            P = self.P[k]
+            g.gcn_dense_fwd(H[:nr], W, P[:nr])
+            g.gcn_spmm_part(A, g.PART_LOCAL, P, out)
+            main.wait_stream(self.side)
+            g.gcn_dense_fwd(H[nr:], W, P[nr:])
+            g.gcn_spmm_part(A, g.PART_HALO, P, out, epilogue=g.EPI_RELU if act == g.ACT_RELU else g.EPI_NONE)
 
 
 def cpu_baseline(w, frac):
@@ -119,6 +152,8 @@ def main():
     ap.add_argument("--workload", default="c2_rmat18")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="block workloads: fetch the halo rows before the layer instead of during its owned-column product")
     ap.add_argument("--cpu-sample-frac", type=float, default=None)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain row copy of known size (for scaling hardware byte counters)")
@@ -169,7 +204,7 @@ def main():
             X = X.to(torch.bfloat16)
     Ws = [torch.from_numpy(m).to(dev) for m in w["W"]]
     y = torch.from_numpy(w["y"]).to(dev)
-    ep = Epoch(gcn, torch, A, X, Ws, y, bf16, table=table)
+    ep = Epoch(gcn, torch, A, X, Ws, y, bf16, table=table, overlap=not args.no_overlap)
     del X
 
     for _ in range(args.warmup):

@@ -187,6 +187,31 @@ int gcn_softmax_xent(const void* Z, int64_t ldz, int64_t nr, int C, int dtype, c
                      float scale, float* loss, void* G, int64_t ldg, void* stream);
 
 /*
+ * The product of gcn_spmm in two steps (Sec. 4.1, block form Z_m = A_m H_m + sum_n A_m H_nm, and
+ * Algorithm 1: the local product does not wait for the rows of other processors):
+ *   GCN_PART_LOCAL  Y = A^[:, 0..nr) X[0..nr)        plain sums; reads only the owned rows of X, so it can run
+ *                                                    while the halo rows are still on their way.  epilogue must
+ *                                                    be GCN_EPI_NONE and bias NULL.
+ *   GCN_PART_HALO   Y = epilogue(Y + A^[:, nr..nc) X[nr..nc) + bias)    adds the halo columns to what the local
+ *                                                    step left in Y and finishes the product.
+ * Arguments as gcn_spmm.  The two steps in this order give gcn_spmm's result up to the order of the additions
+ * (same tolerance); a handle without halo columns takes the second step as "apply the epilogue".
+ */
+#define GCN_PART_LOCAL 1
+#define GCN_PART_HALO 2
+int gcn_spmm_part(const gcn_csr_t* A, int part, const void* X, int64_t ldx, int d, int dtype, void* Y,
+                  int64_t ldy, int epilogue, const float* bias, const void* Zprev, int64_t ldz, void* stream);
+
+/*
+ * The dense half of a layer on `rows` rows (Sec. 3.1: the product with W^k and the activation), for callers
+ * that drive the sparse half themselves (gcn_spmm_part):
+ *   Out = act(X W + bias),  Z (nullable) = X W + bias.   X: device [rows x d_in] (ldx), W: device f32
+ *   [d_in x d_out], Out / Z: device [rows x d_out] (ldo / contiguous), element type dtype.
+ */
+int gcn_dense_fwd(const void* X, int64_t ldx, int64_t rows, const float* W, const float* bias, int d_in, int d_out,
+                  int act, int dtype, void* Z, void* Out, int64_t ldo, void* stream);
+
+/*
  * Weight update of gradient descent (Sec. 3.1, last equation; last line of Algorithm 2):
  *   W <- W - lr * dW,   elementwise on n fp32 values (W and dW: device, contiguous, may not overlap).
  * One fused multiply-add per element.  Not part of the timed forward+backward epoch.

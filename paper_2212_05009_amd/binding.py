@@ -12,6 +12,7 @@ _LIB_PATH = os.path.join(_HERE, "libgcn.so")
 F32, BF16 = 0, 1
 BUILD_CSC = 1
 EPI_NONE, EPI_RELU, EPI_MASK = 0, 1, 2
+PART_LOCAL, PART_HALO = 1, 2
 ACT_NONE, ACT_RELU = 0, 1
 
 
@@ -52,6 +53,10 @@ def _load():
     lib.gcn_layer_fwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]
     lib.gcn_layer_bwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp]
     lib.gcn_softmax_xent.argtypes = [vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, C.c_float, vp, vp, C.c_int64, vp]
+    lib.gcn_spmm_part.argtypes = [vp, C.c_int, vp, C.c_int64, C.c_int, C.c_int, vp, C.c_int64, C.c_int, vp, vp, C.c_int64, vp]
+    lib.gcn_spmm_part.restype = C.c_int
+    lib.gcn_dense_fwd.argtypes = [vp, C.c_int64, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, C.c_int64, vp]
+    lib.gcn_dense_fwd.restype = C.c_int
     lib.gcn_sgd_update.argtypes = [vp, vp, C.c_int64, C.c_float, vp]
     lib.gcn_sgd_update.restype = C.c_int
     lib.gcn_profile_enable.argtypes = [C.c_int]
@@ -197,6 +202,39 @@ def gcn_spmm(A: Csr, X: torch.Tensor, Y: torch.Tensor, epilogue: int = EPI_NONE,
     _check(_lib.gcn_spmm(A.handle, _ptr(X), ldx, d, _dtype_code(X), _ptr(Y), ldy, epilogue, _ptr(bias), _ptr(Zprev),
                          ldz, _stream()), "gcn_spmm")
     return Y
+
+
+def gcn_spmm_part(A: Csr, part: int, X: torch.Tensor, Y: torch.Tensor, epilogue: int = EPI_NONE,
+                  bias: torch.Tensor | None = None, Zprev: torch.Tensor | None = None):
+    ldx, d = _rowmajor(_dev(X), "X"); ldy, dy = _rowmajor(_dev(Y), "Y")
+    if X.shape[0] != A.nc or Y.shape[0] != A.nr or dy != d or Y.dtype != X.dtype:
+        raise TypeError("gcn_spmm_part: X must be [nc, d] and Y [nr, d] of the same dtype")
+    ldz = 0
+    if Zprev is not None:
+        ldz, dz = _rowmajor(_dev(Zprev, X.dtype, "Zprev"), "Zprev")
+        if Zprev.shape[0] != A.nr or dz != d:
+            raise TypeError("gcn_spmm_part: Zprev must be [nr, d]")
+    if bias is not None and (_dev(bias, torch.float32, "bias").numel() != d or not bias.is_contiguous()):
+        raise TypeError("gcn_spmm_part: bias must be a contiguous f32 vector of length d")
+    _check(_lib.gcn_spmm_part(A.handle, int(part), _ptr(X), ldx, d, _dtype_code(X), _ptr(Y), ldy, epilogue, _ptr(bias),
+                              _ptr(Zprev), ldz, _stream()), "gcn_spmm_part")
+    return Y
+
+
+def gcn_dense_fwd(X: torch.Tensor, W: torch.Tensor, Out: torch.Tensor, bias: torch.Tensor | None = None,
+                  act: int = ACT_NONE, Z: torch.Tensor | None = None):
+    ldx, d_in = _rowmajor(_dev(X), "X"); ldo, d_out = _rowmajor(_dev(Out, X.dtype, "Out"), "Out")
+    if _dev(W, torch.float32, "W").shape != (d_in, d_out) or not W.is_contiguous():
+        raise TypeError("gcn_dense_fwd: W must be a contiguous f32 [d_in, d_out]")
+    if Out.shape[0] != X.shape[0]:
+        raise TypeError("gcn_dense_fwd: Out must have the rows of X")
+    if Z is not None and (_dev(Z, X.dtype, "Z").shape != (X.shape[0], d_out) or not Z.is_contiguous()):
+        raise TypeError("gcn_dense_fwd: Z must be a contiguous [rows, d_out]")
+    if bias is not None and (_dev(bias, torch.float32, "bias").numel() != d_out or not bias.is_contiguous()):
+        raise TypeError("gcn_dense_fwd: bias must be a contiguous f32 vector of length d_out")
+    _check(_lib.gcn_dense_fwd(_ptr(X), ldx, X.shape[0], _ptr(W), _ptr(bias), d_in, d_out, act, _dtype_code(X), _ptr(Z),
+                              _ptr(Out), ldo, _stream()), "gcn_dense_fwd")
+    return Out
 
 
 def gcn_spmm_t(A: Csr, X: torch.Tensor, Y: torch.Tensor, epilogue: int = EPI_NONE, Zprev: torch.Tensor | None = None):

@@ -134,6 +134,7 @@ struct gcn_csr {
   int64_t* colptr = nullptr;
   int32_t* rowidx = nullptr;
   float* val_t = nullptr;
+  int64_t* mid = nullptr;  // [nr] first entry of each row whose column is a halo column (null when nh == 0)
   gcn::Schedule sched;     // for A   (rows = owned rows)
   gcn::Schedule sched_t;   // for A^T (rows = local columns)
   void* ws = nullptr;      // scratch workspace, grown on demand
@@ -180,6 +181,10 @@ struct SpmmArgs {
   // true when every row of X, the last one included, is backed by ldx readable elements (library
   // buffers with a padded leading dimension): vector loads may then run past column d
   bool x_rows_padded = false;
+  // a product split by column range (Sec. 4.1, the block form: local part first, then the received rows):
+  // 0 whole rows; 1 entries [ptr[r], mid[r]) and plain store; 2 entries [mid[r], ptr[r+1]) added to Y
+  int part = 0;
+  const int64_t* mid = nullptr;
   gcn_csr* owner = nullptr;  // handle the arrays belong to (lets the launch cache a panel plan); may be null
 };
 // ws: workspace for hub partial sums, at least spmm_ws_bytes(sched, d)

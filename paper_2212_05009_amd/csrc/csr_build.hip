@@ -119,6 +119,19 @@ __global__ void k_row_lengths(const int64_t* __restrict__ ptr, int64_t n, int32_
   if (i < n) len[i] = (int32_t)(ptr[i + 1] - ptr[i]);
 }
 
+// first entry of each row whose (local) column is >= nr: columns are ascending, so the owned columns come first
+__global__ void k_row_mid(const int64_t* __restrict__ ptr, const int32_t* __restrict__ col, int64_t nr,
+                          int64_t* __restrict__ mid) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nr) return;
+  int64_t lo = ptr[i], hi = ptr[i + 1];
+  while (lo < hi) {
+    const int64_t m = (lo + hi) >> 1;
+    if (col[m] < nr) lo = m + 1; else hi = m;
+  }
+  mid[i] = lo;
+}
+
 // ---- step 5: values ---------------------------------------------------------------------------------
 // val(i,j) = fl(1/sqrt(d_i)) * fl(1/sqrt(d_j)), each operation correctly rounded in fp32.
 // Both steps go through fp64: an fp64 square root or quotient rounded once more to fp32 equals the
@@ -357,6 +370,13 @@ static int build_impl(const int32_t* d_src, const int32_t* d_dst, int64_t n_edge
                                                halo_gid.as<int32_t>(), val.as<float>());
   GCN_CHECK_LAUNCH();
 
+  DevBuf mid;
+  if (nh > 0) {
+    GCN_TRY(mid.alloc(sizeof(int64_t) * (size_t)nr));
+    k_row_mid<<<grid_for(nr), kThreads, 0, s>>>(rowptr.as<int64_t>(), col.as<int32_t>(), nr, mid.as<int64_t>());
+    GCN_CHECK_LAUNCH();
+  }
+
   // -- column-major copy
   DevBuf colptr, rowidx, val_t;
   if (flags & GCN_BUILD_CSC) {
@@ -391,6 +411,7 @@ static int build_impl(const int32_t* d_src, const int32_t* d_dst, int64_t n_edge
   A->halo_gid = (int32_t*)halo_gid.release();
   A->colptr = (int64_t*)colptr.release(); A->rowidx = (int32_t*)rowidx.release();
   A->val_t = (float*)val_t.release();
+  A->mid = nh > 0 ? (int64_t*)mid.release() : nullptr;
   return GCN_OK;
 }
 
@@ -468,7 +489,7 @@ extern "C" int gcn_csr_arrays(const gcn_csr_t* A, const int64_t** rowptr, const 
 extern "C" int gcn_csr_free(gcn_csr_t* A) {
   if (!A) return GCN_OK;
   (void)hipDeviceSynchronize();
-  void* ptrs[] = {A->rowptr, A->col, A->val, A->deg, A->halo_gid, A->colptr, A->rowidx, A->val_t, A->ws};
+  void* ptrs[] = {A->rowptr, A->col, A->val, A->deg, A->halo_gid, A->colptr, A->rowidx, A->val_t, A->mid, A->ws};
   for (void* p : ptrs) if (p) (void)hipFree(p);
   free_schedule(&A->sched);
   free_schedule(&A->sched_t);

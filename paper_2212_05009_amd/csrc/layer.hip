@@ -153,3 +153,17 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
   }
   return GCN_OK;
 }
+
+extern "C" int gcn_dense_fwd(const void* X, int64_t ldx, int64_t rows, const float* W, const float* bias, int d_in,
+                             int d_out, int act, int dtype, void* Z, void* Out, int64_t ldo, void* stream) {
+  clear_error();
+  if (rows < 0) return fail(GCN_EINVAL, "gcn_dense_fwd: negative row count");
+  if (rows == 0) return GCN_OK;
+  if (!X || !W || !Out) return fail(GCN_EINVAL, "gcn_dense_fwd: NULL argument");
+  if (d_in < 1 || d_out < 1 || ldx < d_in || ldo < d_out) return fail(GCN_EINVAL, "gcn_dense_fwd: bad dimensions");
+  if (act != GCN_ACT_NONE && act != GCN_ACT_RELU) return fail(GCN_EINVAL, "gcn_dense_fwd: unknown activation");
+  if (dtype != GCN_F32 && dtype != GCN_BF16) return fail(GCN_EINVAL, "gcn_dense_fwd: unknown dtype");
+  GemmEpilogue epi;
+  epi.bias = bias; epi.relu = act == GCN_ACT_RELU; epi.C2 = Z; epi.ldc2 = d_out;
+  return gemm_nn(X, ldx, W, d_out, Out, ldo, rows, d_out, d_in, dtype, epi, (hipStream_t)stream);
+}

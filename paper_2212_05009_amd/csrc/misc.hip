@@ -1,6 +1,7 @@
 // Error bookkeeping, the halo gather and the softmax cross-entropy of the gfx950 GCN library.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 
 #include "common.h"
 
@@ -52,12 +53,74 @@ __global__ __launch_bounds__(256) void k_gather(const char* __restrict__ table, 
   }
 }
 
+// The same copy for a table in host memory: the link to the host, not the GPU, sets the pace, and a
+// few hundred rows in flight saturate it (measured: 16 workgroups reach the rate of a full grid, 8
+// do not).  A few workgroups (32; GCN_GATHER_HOST_BLOCKS overrides) walk the index list with
+// kGatherRows rows in flight per lane group; the rest of the GPU stays free for kernels of other
+// streams, which a full grid of waiting wavefronts slows down several times over (the product with
+// the owned columns runs meanwhile, Algorithm 1).
+constexpr int kGatherRows = 4;
+template <int VB, int LPR>
+__global__ __launch_bounds__(256) void k_gather_host(const char* __restrict__ table, int64_t ld_bytes,
+                                                     int64_t n_table_rows, int n_vec,
+                                                     const int32_t* __restrict__ idx, int64_t n_idx,
+                                                     char* __restrict__ recv, int64_t ldr_bytes) {
+  typedef typename Unit<VB>::type U;
+  constexpr int G = 256 / LPR;
+  const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
+  const int64_t stride = (int64_t)gridDim.x * G;
+  for (int64_t s0 = (int64_t)blockIdx.x * G + g; s0 < n_idx; s0 += stride * kGatherRows) {
+    const U* src[kGatherRows]; bool ok[kGatherRows];
+#pragma unroll
+    for (int r = 0; r < kGatherRows; ++r) {
+      const int64_t s = s0 + r * stride;
+      const int64_t j = s < n_idx ? (int64_t)idx[s] : -1;
+      ok[r] = j >= 0 && j < n_table_rows;
+      src[r] = reinterpret_cast<const U*>(table + (ok[r] ? j : 0) * ld_bytes);
+    }
+    for (int u = l; u < n_vec; u += LPR) {
+      U v[kGatherRows];
+#pragma unroll
+      for (int r = 0; r < kGatherRows; ++r) {
+        if (ok[r]) v[r] = src[r][u];
+        else memset(&v[r], 0, sizeof(U));
+      }
+#pragma unroll
+      for (int r = 0; r < kGatherRows; ++r) {
+        const int64_t s = s0 + r * stride;
+        if (s < n_idx) reinterpret_cast<U*>(recv + s * ldr_bytes)[u] = v[r];
+      }
+    }
+  }
+}
+
+static bool is_host_memory(const void* p) {
+  hipPointerAttribute_t at;
+  if (hipPointerGetAttributes(&at, p) != hipSuccess) { (void)hipGetLastError(); return false; }
+  return at.type == hipMemoryTypeHost;
+}
+
 template <int VB>
 static int gather_v(const char* table, int64_t ldb, int64_t nt, int n_vec, const int32_t* idx, int64_t n_idx,
                     char* recv, int64_t ldrb, int d, int dtype, hipStream_t s) {
   auto grid = [&](int lpr) { return dim3((unsigned)ceil_div(n_idx, 256 / lpr)); };
   const double by = 2.0 * (double)n_idx * n_vec * VB + 4.0 * (double)n_idx;
   ProfScope ps(GCN_K_GATHER, s, d, dtype, n_idx, 0, by, by, 0.0);
+  if (is_host_memory(table)) {
+    static const int host_blocks = [] {
+      const char* e = getenv("GCN_GATHER_HOST_BLOCKS");
+      const int v = e ? atoi(e) : 0;
+      return v >= 1 && v <= 4096 ? v : 32;
+    }();
+    const unsigned nb = (unsigned)std::min<int64_t>(host_blocks, ceil_div(n_idx, 8));
+    if (n_vec <= 4) k_gather_host<VB, 4><<<nb, 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
+    else if (n_vec <= 8) k_gather_host<VB, 8><<<nb, 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
+    else if (n_vec <= 16) k_gather_host<VB, 16><<<nb, 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
+    else if (n_vec <= 32) k_gather_host<VB, 32><<<nb, 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
+    else k_gather_host<VB, 64><<<nb, 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
+    GCN_CHECK_LAUNCH();
+    return GCN_OK;
+  }
   if (n_vec <= 4) k_gather<VB, 4><<<grid(4), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
   else if (n_vec <= 8) k_gather<VB, 8><<<grid(8), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
   else if (n_vec <= 16) k_gather<VB, 16><<<grid(16), 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);

@@ -44,8 +44,11 @@ static int pick_slices(const SpmmArgs& a, size_t es) {
 }
 
 int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
-  SpmmK k;
+  SpmmK k{};
   k.ptr = a.ptr; k.idx = a.idx; k.val = a.val;
+  k.lo = a.part == 2 ? a.mid : a.ptr;
+  k.hi = a.part == 1 ? a.mid : a.ptr + 1;
+  k.accumulate = a.part == 2 ? 1 : 0;
   k.wave_rows = a.sched->wave_rows;
   k.hub_rows = a.sched->hub_rows; k.hub_chunk_ptr = a.sched->hub_chunk_ptr;
   k.chunk_hub = a.sched->chunk_hub; k.n_chunks = a.sched->n_chunks; k.n_hub_rows = a.sched->n_hub_rows;
@@ -54,7 +57,7 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
   k.partial = (float*)ws; k.d = a.d; k.epilogue = a.epilogue;
   if (a.n_rows == 0) return GCN_OK;
   bool swept = false;
-  GCN_TRY(spmm_panel_try(a, s, &swept));
+  if (a.part == 0) GCN_TRY(spmm_panel_try(a, s, &swept));       // the column-sweep plan covers whole rows only
   if (swept) return GCN_OK;
   const size_t es = a.dtype == GCN_BF16 ? 2 : 4;
   // widest vector such that every feature-row load stays aligned (and inside the row's storage)
@@ -118,5 +121,28 @@ extern "C" int gcn_spmm_t(const gcn_csr_t* A, const void* X, int64_t ldx, int d,
   SpmmArgs a{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, X, ldx, Y, ldy, nullptr, 0,
              d, dtype, epilogue, nullptr, Zprev, ldz};
   a.owner = Am;
+  return spmm_launch(a, Am->ws, (hipStream_t)stream);
+}
+
+extern "C" int gcn_spmm_part(const gcn_csr_t* A, int part, const void* X, int64_t ldx, int d, int dtype, void* Y,
+                             int64_t ldy, int epilogue, const float* bias, const void* Zprev, int64_t ldz, void* stream) {
+  clear_error();
+  if (!A) return fail(GCN_EINVAL, "gcn_spmm_part: NULL handle");
+  if (part != GCN_PART_LOCAL && part != GCN_PART_HALO) return fail(GCN_EINVAL, "gcn_spmm_part: part must be GCN_PART_LOCAL or GCN_PART_HALO");
+  GCN_TRY(check_dense("gcn_spmm_part", X, ldx, Y, ldy, d, dtype));
+  if (epilogue < GCN_EPI_NONE || epilogue > GCN_EPI_MASK) return fail(GCN_EINVAL, "gcn_spmm_part: unknown epilogue");
+  if (part == GCN_PART_LOCAL && (epilogue != GCN_EPI_NONE || bias))
+    return fail(GCN_EINVAL, "gcn_spmm_part: the local part stores plain sums; bias and epilogue belong to the halo part");
+  if (epilogue == GCN_EPI_MASK && (!Zprev || ldz < d)) return fail(GCN_EINVAL, "gcn_spmm_part: mask epilogue needs Zprev with ldz >= d");
+  gcn_csr* Am = const_cast<gcn_csr*>(A);
+  GCN_TRY(ensure_workspace(Am, spmm_ws_bytes(&A->sched, d)));
+  SpmmArgs a{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, X, ldx, Y, ldy, nullptr, 0,
+             d, dtype, epilogue, bias, Zprev, ldz};
+  a.owner = Am;
+  if (A->mid) { a.part = part; a.mid = A->mid; }
+  else if (part == GCN_PART_HALO) {
+    // no halo columns: the local part was the whole product; only the epilogue is left to apply
+    a.part = 2; a.mid = A->rowptr + 1;            // empty ranges [ptr[r+1], ptr[r+1])
+  }
   return spmm_launch(a, Am->ws, (hipStream_t)stream);
 }

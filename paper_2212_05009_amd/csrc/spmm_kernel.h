@@ -59,6 +59,9 @@ constexpr int kMaxBins = 34;
 
 struct SpmmK {
   const int64_t* ptr; const int32_t* idx; const float* val;
+  // entries of row r that take part: [lo[r], hi[r]); the whole row is lo = ptr, hi = ptr + 1
+  const int64_t* lo; const int64_t* hi;
+  int accumulate;     // 1: the result is added to what Y holds (a product split in two column ranges)
   const int32_t* wave_rows;
   const int32_t* hub_rows; const int64_t* hub_chunk_ptr; const int32_t* chunk_hub; int64_t n_chunks;
   int64_t n_hub_rows;
@@ -190,6 +193,7 @@ __device__ __forceinline__ void reduce_groups(float (&acc)[V], int groups) {
 // epilogue on one element of output row `row`, feature c
 template <typename T>
 __device__ __forceinline__ void finish_element(const SpmmK& a, int64_t row, int64_t c, float v) {
+  if (a.accumulate) v += load_one<T>(reinterpret_cast<const T*>(a.Y) + row * a.ldy + c);
   if (a.bias) v += a.bias[c];
   if (a.Y2) store_one<T>(reinterpret_cast<T*>(a.Y2) + row * a.ldy2 + c, v);
   if (a.epilogue == GCN_EPI_RELU) v = v > 0.f ? v : 0.f;
@@ -203,6 +207,12 @@ __device__ __forceinline__ void finish_element(const SpmmK& a, int64_t row, int6
 // the same on V consecutive elements, written with one vector store per output
 template <typename T, int V>
 __device__ __forceinline__ void finish_vector(const SpmmK& a, int64_t row, int64_t c0, float (&v)[V]) {
+  if (a.accumulate) {
+    float old[V];
+    load_vec<T, V>(reinterpret_cast<const T*>(a.Y) + row * a.ldy + c0, old);
+#pragma unroll
+    for (int i = 0; i < V; ++i) v[i] += old[i];
+  }
   if (a.bias) {
 #pragma unroll
     for (int i = 0; i < V; ++i) v[i] += a.bias[c0 + i];
@@ -238,9 +248,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     const int64_t c = item;
     const int32_t h = a.chunk_hub[c];
     const int64_t row = a.hub_rows[h];
-    const int64_t s = a.ptr[row] + (c - a.hub_chunk_ptr[h]) * kHubChunkNnz;
-    const int64_t row_end = a.ptr[row + 1];
-    const int64_t e = s + kHubChunkNnz < row_end ? s + kHubChunkNnz : row_end;
+    const int64_t cs = a.ptr[row] + (c - a.hub_chunk_ptr[h]) * kHubChunkNnz;      // chunks are cut from the whole row
+    const int64_t row_lo = a.lo[row], row_hi = a.hi[row];
+    const int64_t s = cs > row_lo ? cs : row_lo;
+    const int64_t e = cs + kHubChunkNnz < row_hi ? cs + kHubChunkNnz : row_hi;
     const int64_t ws = s + (int64_t)w * (kHubChunkNnz / 4);
     const int64_t we = ws + kHubChunkNnz / 4 < e ? ws + kHubChunkNnz / 4 : e;
     for (int t0 = v_lo; t0 < v_hi; t0 += LPR) {
@@ -277,7 +288,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
   const int64_t ri = a.bin_row_begin[b] + (wi - a.bin_wave_begin[b]) * (G >> lgr) + q;
   const bool has_row = ri < a.bin_row_end[b];
   int64_t row = 0, s = 0, e = 0;
-  if (has_row) { row = a.wave_rows[ri]; s = a.ptr[row]; e = a.ptr[row + 1]; }
+  if (has_row) { row = a.wave_rows[ri]; s = a.lo[row]; e = a.hi[row]; }
   for (int t0 = v_lo; t0 < v_hi; t0 += LPR) {
     const int vi = t0 + l;
     const bool active = vi < v_hi;

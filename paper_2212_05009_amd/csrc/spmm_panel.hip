@@ -769,7 +769,7 @@ int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used) {
     a.owner->plans.push_back(P);
   }
 
-  PanelK k;
+  PanelK k{};                // (zeroes the fields of the embedded SpmmK that this kernel does not use)
   k.k.X = a.X; k.k.ldx = a.ldx; k.k.Y = a.Y; k.k.ldy = a.ldy; k.k.Y2 = a.Y2; k.k.ldy2 = a.ldy2;
   k.k.bias = a.bias; k.k.Zprev = a.Zprev; k.k.ldz = a.ldz; k.k.n_mask_rows = a.n_mask_rows;
   k.k.d = a.d; k.k.epilogue = a.epilogue; k.k.row_bytes = (uint32_t)(a.ldx * (int64_t)es);

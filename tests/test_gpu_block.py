@@ -2,6 +2,8 @@
 (the shape of the largest workload at 1/32 of its size, same generator, same Epoch call sequence as
 bench.py): halo index list and remapped CSR/CSC bit for bit, gathered rows bit for bit, sampled rows of
 the forward and backward results and every element of the weight gradients within 1e-5 * sum|terms|.
+Run twice: with the halo fetch overlapped with the owned-column products (two-step sparse product), and
+with the fetch before each layer (one-step product).
 """
 import numpy as np
 import pytest
@@ -12,8 +14,8 @@ from util import TOL_F32, check_bound, say
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module")
-def blk():
+@pytest.fixture(scope="module", params=[True, False], ids=["overlapped", "sequential"])
+def blk(request):
     import torch
     import bench
     import paper_2212_05009_amd as gcn
@@ -29,8 +31,9 @@ def blk():
     tab = torch.empty((n, w["dims"][0]), dtype=torch.float32, pin_memory=True)
     wtable.fill_table_torch(tab, w["table_seed"], dev)
     Ws = [torch.from_numpy(m).to(dev) for m in w["W"]]
-    ep = bench.Epoch(gcn, torch, A, tab[lo:hi].to(dev), Ws, torch.from_numpy(w["y"]).to(dev), False, table=tab)
-    say("block epoch with halo gathers from the pinned host table")
+    ep = bench.Epoch(gcn, torch, A, tab[lo:hi].to(dev), Ws, torch.from_numpy(w["y"]).to(dev), False, table=tab,
+                     overlap=request.param)
+    say(f"block epoch with halo gathers from the pinned host table, overlap={request.param}")
     ep.run()
     ep.run()
     torch.cuda.synchronize()

@@ -185,6 +185,30 @@ def test_gather_device_table(gcn, dev, d, bf16):
     assert np.array_equal(to_np(recv).view(np.int32), want.view(np.int32))
 
 
+@pytest.mark.parametrize("d", [1, 3, 32, 100, 128, 602])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_gather_host_table_widths(gcn, dev, d, bf16):
+    """Pinned host table: the narrow launch (a few rows in flight per lane group), ragged tail, bad ids."""
+    import torch
+    rng = np.random.default_rng(50 + d)
+    T = rng.standard_normal((3000, d)).astype(np.float32)
+    if bf16:
+        T = bf16_round(T)
+    for n_idx in (1, 37, 9001):
+        idx = rng.integers(0, 3000, n_idx).astype(np.int32)
+        if n_idx > 30:
+            idx[5] = 3000; idx[n_idx - 1] = -7
+        want = oracle.gather(T, np.where((idx >= 0) & (idx < 3000), idx, 0))
+        want[(idx < 0) | (idx >= 3000)] = 0
+        Th = (torch.from_numpy(T).to(torch.bfloat16) if bf16 else torch.from_numpy(T)).pin_memory()
+        recv = torch.full((n_idx + 2, d), 3.0, dtype=Th.dtype, device=dev)
+        say(f"gather host d={d} bf16={bf16} n_idx={n_idx}")
+        gcn.gcn_halo_gather(Th, to_dev(idx, dev), recv[:n_idx])
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(recv[:n_idx]).view(np.int32), want.view(np.int32))
+        assert bool((recv[n_idx:].float() == 3.0).all()), "wrote past the last row"
+
+
 def test_gather_pinned_host_table_and_edge_cases(gcn, dev):
     import torch
     rng = np.random.default_rng(4)
