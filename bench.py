@@ -35,7 +35,7 @@ class Epoch:
     other processors would send) at the start of that layer, inside the timed epoch.
     """
 
-    def __init__(self, gcn, torch, A, X_owned, Ws, y, bf16, table=None, overlap=True):
+    def __init__(self, gcn, torch, A, X_owned, Ws, y, bf16, table=None, overlap=True, backward="push"):
         self.gcn, self.torch, self.A, self.Ws, self.y, self.table = gcn, torch, A, Ws, y, table
         dev = X_owned.device
         fdt = torch.bfloat16 if bf16 else torch.float32
@@ -52,8 +52,16 @@ class Epoch:
         self.Zlast = torch.empty(nr, dims[self.L], dtype=fdt, device=dev)
         # D[k]: gradient w.r.t. the input rows of layer k+1 ([nc, dims[k+1]]: owned rows, then this block's
         # contributions to halo rows); its owned rows are G[k], the gradient w.r.t. Z of layer k
-        self.D = [torch.empty(nc, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L - 1)]
-        self.G = [d[:nr] for d in self.D] + [torch.empty(nr, dims[self.L], dtype=fdt, device=dev)]
+        # backward="pull" (Algorithm 2, symmetric graphs): D[k] holds the owned rows of G^k, complete, followed by
+        # the halo rows of G^k fetched like those of H (from the table, the stand-in for what other processors
+        # hold); the last layer then needs the full height too, and T[k] receives A^ [G; G_halo]
+        assert backward in ("push", "pull")
+        self.pull = backward == "pull"
+        self.D = [torch.empty(nc, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L if self.pull else self.L - 1)]
+        self.G = [d[:nr] for d in self.D] + ([] if self.pull else [torch.empty(nr, dims[self.L], dtype=fdt, device=dev)])
+        if self.pull:
+            assert table is None or max(dims[1:]) <= table.shape[1], "the stand-in table is narrower than a gradient row"
+            self.T = [torch.empty(nr, dims[k + 1], dtype=fdt, device=dev) for k in range(self.L)]
         # A^ H is kept for the weight gradient where the forward pass computes it anyway
         self.AH = [torch.empty(nr, dims[k], dtype=fdt, device=dev) if dims[k] <= dims[k + 1] else None
                    for k in range(self.L)]
@@ -81,9 +89,31 @@ class Epoch:
             g.gcn_layer_fwd(A, self.H[k], self.Ws[k], out, act=act, AH_save=self.AH[k])
         g.gcn_softmax_xent(self.Zlast, self.y, 1.0 / nr, self.loss, self.G[L - 1])
         for k in range(L - 1, -1, -1):
+            if self.pull:
+                self.backward_pull(k)
+                continue
             g.gcn_layer_bwd(A, self.H[k], self.Ws[k], self.G[k], self.dW[k],
                             dH=self.D[k - 1] if k > 0 else None, Zprev=self.H[k][:nr] if k > 0 else None,
                             AH_saved=self.AH[k])
+
+    def backward_pull(self, k):
+        """Layer k backward as Algorithm 2: fetch the halo rows of G^k, T = A^ [G; G_halo], dH and dW from T."""
+        g, A, torch, nr = self.gcn, self.A, self.torch, self.A.nr
+        D, d = self.D[k], self.dims[k + 1]
+        args = dict(dH=self.D[k - 1][:nr] if k > 0 else None, Zprev=self.H[k][:nr] if k > 0 else None)
+        if not A.nh:
+            g.gcn_layer_bwd_pull(A, self.H[k], self.Ws[k], D, self.T[k], self.dW[k], **args)
+        elif not self.overlap:
+            g.gcn_halo_gather(self.table[:, :d], self.halo_gid, D[nr:])
+            g.gcn_layer_bwd_pull(A, self.H[k], self.Ws[k], D, self.T[k], self.dW[k], **args)
+        else:
+            main = torch.cuda.current_stream()
+            self.side.wait_stream(main)
+            with torch.cuda.stream(self.side):
+                g.gcn_halo_gather(self.table[:, :d], self.halo_gid, D[nr:])
+            g.gcn_layer_bwd_pull(A, self.H[k], self.Ws[k], D, self.T[k], self.dW[k], phase=g.PART_LOCAL)
+            main.wait_stream(self.side)
+            g.gcn_layer_bwd_pull(A, self.H[k], self.Ws[k], D, self.T[k], self.dW[k], phase=g.PART_HALO, **args)
 
 
     def forward_overlapped(self, k, out, act):
@@ -152,6 +182,9 @@ def main():
     ap.add_argument("--workload", default="c2_rmat18")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--backward", default="push", choices=["push", "pull"],
+                    help="push: dH = A^T (G W^T) with contributions to halo rows (the default, any graph); "
+                         "pull: Algorithm 2, halo rows of G fetched and T = A [G; G_halo] shared by dH and dW (symmetric graphs)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="block workloads: fetch the halo rows before the layer instead of during its owned-column product")
     ap.add_argument("--cpu-sample-frac", type=float, default=None)
@@ -204,7 +237,7 @@ def main():
             X = X.to(torch.bfloat16)
     Ws = [torch.from_numpy(m).to(dev) for m in w["W"]]
     y = torch.from_numpy(w["y"]).to(dev)
-    ep = Epoch(gcn, torch, A, X, Ws, y, bf16, table=table, overlap=not args.no_overlap)
+    ep = Epoch(gcn, torch, A, X, Ws, y, bf16, table=table, overlap=not args.no_overlap, backward=args.backward)
     del X
 
     for _ in range(args.warmup):
@@ -302,7 +335,7 @@ def main():
     out = {"metric": "GCN full-batch epoch ms (fwd+bwd) on 1 MI355X", "value": round(ms_per_step, 4), "unit": "ms/epoch",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
            "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-           "config": {"workload": args.workload, "n": n, "owned_rows": A.nr, "halo_rows": A.nh, "nnz": A.nnz, "dims": dims,
+           "config": {"workload": args.workload, "backward": args.backward, "halo_overlap": ep.overlap, "n": n, "owned_rows": A.nr, "halo_rows": A.nh, "nnz": A.nnz, "dims": dims,
                       "layers": len(dims) - 1},
            "epochs_per_s": round(1e3 / ms_per_step, 2), "loss": round(loss, 6), "csr_csc_build_ms": round(build_ms, 2),
            "roofline": roof, "kernels": kernels, "kernels_from": f"a separate pass of {bsteps} epochs with every launch timed",

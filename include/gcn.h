@@ -212,6 +212,26 @@ int gcn_dense_fwd(const void* X, int64_t ldx, int64_t rows, const float* W, cons
                   int act, int dtype, void* Z, void* Out, int64_t ldo, void* stream);
 
 /*
+ * Backward pass of one layer in the form of Algorithm 2 (Sec. 4.2), for a symmetric A^: every block pulls the
+ * gradient rows it needs instead of pushing contributions.
+ *   T     = A^_m [G_m; G_halo]               [nr x d_out] (ld = d_out), element type dtype: the product that serves
+ *                                            both results below; written to the caller's buffer T.
+ *   dH    = (T W^T) (.) [Zprev > 0]          [nr x d_in] (ld = d_in) or NULL: the owned rows of G^(k-1), complete
+ *                                            (nothing to send back).  Zprev [nr x d_in] (ld = d_in); NULL = no mask.
+ *   dW    = H_m^T T                          f32 [d_in x d_out]: this block's partial sum; only the nr owned rows
+ *                                            of H (ldh) are read.
+ *   dbias = column sums of the owned rows of G, f32 [d_out] or NULL.
+ *   G     device [nc x d_out] (ldg): owned rows, then the halo rows in halo-list order (fetched by the caller, e.g.
+ *         with gcn_halo_gather, as the rows of H are in the forward pass).
+ *   phase 0: everything.  GCN_PART_LOCAL: only T = A^[:, 0..nr) G_m, which reads no halo row of G and can run while
+ *         those arrive (H, W, dW may be NULL).  GCN_PART_HALO: adds the halo columns to T, then dH, dW, dbias.
+ * On a directed graph this is not the gradient (the algorithm relies on A^ = A^T); gcn_layer_bwd is.
+ */
+int gcn_layer_bwd_pull(const gcn_csr_t* A, int phase, const void* H, int64_t ldh, const float* W, int d_in, int d_out,
+                       int dtype, const void* G, int64_t ldg, const void* Zprev, void* T, float* dW, float* dbias,
+                       void* dH, void* stream);
+
+/*
  * Weight update of gradient descent (Sec. 3.1, last equation; last line of Algorithm 2):
  *   W <- W - lr * dW,   elementwise on n fp32 values (W and dW: device, contiguous, may not overlap).
  * One fused multiply-add per element.  Not part of the timed forward+backward epoch.

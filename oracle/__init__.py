@@ -183,6 +183,23 @@ def layer_bwd(g: Graph, H, W, G, Zprev=None, want_dH=True, want_dbias=False):
     return {"dW": dW, "BdW": BdW, "dH": dH, "BdH": BdH, "dbias": db, "Bdb": Bdb}
 
 
+def layer_bwd_pull(g: Graph, H_owned, W, G_all, Zprev=None):
+    """Backward pass of one layer as Algorithm 2 (Sec. 4.2) states it for processor m, steps in its order:
+    T = A_m [G_m; G_halo] (the by-product), S = T W^T, G^(k-1)_m = S (.) [Zprev > 0], dW_m = H_m^T T.
+    Returns dict(T, BT, dH, BdH, dW, BdW) in fp64; B* are the same sums over absolute values."""
+    H_owned, W, G_all = _f32(H_owned), _f32(W), _f32(G_all)
+    d_in, d_out = W.shape
+    assert H_owned.shape == (g.nr, d_in) and G_all.shape == (g.nc, d_out)
+    T, BT = spmm(g.rowptr, g.col, g.val, G_all)
+    W64, H64 = W.astype(np.float64), H_owned.astype(np.float64)
+    S, BS = T @ W64.T, BT @ np.abs(W64).T
+    if Zprev is not None:
+        keep = _f32(Zprev) > 0
+        assert keep.shape == S.shape
+        S = np.where(keep, S, 0.0)
+    return {"T": T, "BT": BT, "dH": S, "BdH": BS, "dW": H64.T @ T, "BdW": np.abs(H64).T @ BT}
+
+
 def softmax_xent(Z, y, scale):
     """Returns (loss, loss_bound, G) in fp64."""
     Z = _f32(Z)

@@ -57,6 +57,8 @@ def _load():
     lib.gcn_spmm_part.restype = C.c_int
     lib.gcn_dense_fwd.argtypes = [vp, C.c_int64, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, C.c_int64, vp]
     lib.gcn_dense_fwd.restype = C.c_int
+    lib.gcn_layer_bwd_pull.argtypes = [vp, C.c_int, vp, C.c_int64, vp, C.c_int, C.c_int, C.c_int, vp, C.c_int64, vp, vp, vp, vp, vp, vp]
+    lib.gcn_layer_bwd_pull.restype = C.c_int
     lib.gcn_sgd_update.argtypes = [vp, vp, C.c_int64, C.c_float, vp]
     lib.gcn_sgd_update.restype = C.c_int
     lib.gcn_profile_enable.argtypes = [C.c_int]
@@ -310,6 +312,27 @@ def gcn_layer_bwd(A: Csr, H: torch.Tensor, W: torch.Tensor, G: torch.Tensor, dW:
         _dense(dbias.view(1, -1), 1, d_out, torch.float32, "dbias")
     _check(_lib.gcn_layer_bwd(A.handle, _ptr(H), ldh, _ptr(AH_saved), _ptr(W), d_in, d_out, _dtype_code(H), _ptr(G),
                               _ptr(Zprev), _ptr(dW), _ptr(dbias), _ptr(dH), _stream()), "gcn_layer_bwd")
+    return dW
+
+
+def gcn_layer_bwd_pull(A: Csr, H: torch.Tensor, W: torch.Tensor, G: torch.Tensor, T: torch.Tensor, dW: torch.Tensor,
+                       dH: torch.Tensor | None = None, Zprev: torch.Tensor | None = None,
+                       dbias: torch.Tensor | None = None, phase: int = 0):
+    """H needs only its nr owned rows ([>= nr, d_in]); G is [nc, d_out]; T [nr, d_out]; dH [nr, d_in]."""
+    ldh, d_in = _rowmajor(_dev(H), "H")
+    ldg, d_out = _rowmajor(_dev(G, H.dtype, "G"), "G")
+    if H.shape[0] < A.nr or G.shape[0] != A.nc:
+        raise TypeError("gcn_layer_bwd_pull: H must hold the nr owned rows and G all nc rows")
+    _dense(W, d_in, d_out, torch.float32, "W"); _dense(dW, d_in, d_out, torch.float32, "dW")
+    _dense(T, A.nr, d_out, H.dtype, "T")
+    if dH is not None:
+        _dense(dH, A.nr, d_in, H.dtype, "dH")
+    if Zprev is not None:
+        _dense(Zprev, A.nr, d_in, H.dtype, "Zprev")
+    if dbias is not None:
+        _dense(dbias.view(1, -1), 1, d_out, torch.float32, "dbias")
+    _check(_lib.gcn_layer_bwd_pull(A.handle, int(phase), _ptr(H), ldh, _ptr(W), d_in, d_out, _dtype_code(H), _ptr(G), ldg,
+                                   _ptr(Zprev), _ptr(T), _ptr(dW), _ptr(dbias), _ptr(dH), _stream()), "gcn_layer_bwd_pull")
     return dW
 
 

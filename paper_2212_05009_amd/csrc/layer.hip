@@ -167,3 +167,49 @@ extern "C" int gcn_dense_fwd(const void* X, int64_t ldx, int64_t rows, const flo
   epi.bias = bias; epi.relu = act == GCN_ACT_RELU; epi.C2 = Z; epi.ldc2 = d_out;
   return gemm_nn(X, ldx, W, d_out, Out, ldo, rows, d_out, d_in, dtype, epi, (hipStream_t)stream);
 }
+
+extern "C" int gcn_layer_bwd_pull(const gcn_csr_t* A, int phase, const void* H, int64_t ldh, const float* W, int d_in,
+                                  int d_out, int dtype, const void* G, int64_t ldg, const void* Zprev, void* T,
+                                  float* dW, float* dbias, void* dH, void* stream) {
+  clear_error();
+  if (!A || !G || !T) return fail(GCN_EINVAL, "gcn_layer_bwd_pull: NULL argument");
+  if (phase != 0 && phase != GCN_PART_LOCAL && phase != GCN_PART_HALO)
+    return fail(GCN_EINVAL, "gcn_layer_bwd_pull: phase must be 0, GCN_PART_LOCAL or GCN_PART_HALO");
+  if (d_in < 1 || d_out < 1 || ldg < d_out) return fail(GCN_EINVAL, "gcn_layer_bwd_pull: bad dimensions");
+  if (dtype != GCN_F32 && dtype != GCN_BF16) return fail(GCN_EINVAL, "gcn_layer_bwd_pull: unknown dtype");
+  const bool finish = phase != GCN_PART_LOCAL;
+  if (finish && (!H || !W || !dW || ldh < d_in)) return fail(GCN_EINVAL, "gcn_layer_bwd_pull: H, W and dW are needed to finish");
+  gcn_csr* Am = const_cast<gcn_csr*>(A);
+  hipStream_t s = (hipStream_t)stream;
+
+  for (int pass = 0; pass < 2; ++pass) {
+    Carver ws{pass ? (char*)Am->ws : nullptr};
+    void* hub = ws.take(spmm_ws_bytes(&A->sched, d_out));
+    float* Wt = finish && dH ? (float*)ws.take(sizeof(float) * (size_t)d_in * d_out) : nullptr;
+    void* cs = finish && dbias ? ws.take(colsum_ws_bytes(A->nr, d_out)) : nullptr;
+    void* tn = finish ? ws.take(gemm_tn_ws_bytes(A->nr, d_in, d_out)) : nullptr;
+    if (pass) {
+      // T = A^_m [G_m; G_halo]: the product that serves both S and dW (Sec. 4.2)
+      SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, G, ldg, T, d_out, nullptr, 0,
+                  d_out, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+      sp.owner = Am;
+      if (phase != 0) {
+        if (A->mid) { sp.part = phase; sp.mid = A->mid; }
+        else if (phase == GCN_PART_HALO) { sp.part = 2; sp.mid = A->rowptr + 1; }
+      }
+      GCN_TRY(spmm_launch(sp, hub, s));
+      if (finish) {
+        if (dbias) GCN_TRY(colsum(G, ldg, A->nr, d_out, dtype, dbias, cs, s));
+        if (dH) {
+          GCN_TRY(transpose_f32(W, d_in, d_out, Wt, s));
+          GemmEpilogue epi;
+          epi.mask = Zprev; epi.ldmask = d_in; epi.mask_rows = Zprev ? A->nr : 0;
+          GCN_TRY(gemm_nn(T, d_out, Wt, d_in, dH, d_in, A->nr, d_in, d_out, dtype, epi, s));
+        }
+        GCN_TRY(gemm_tn(H, ldh, T, d_out, dW, d_out, A->nr, d_in, d_out, dtype, tn, s));
+      }
+    }
+    if (!pass) GCN_TRY(ensure_workspace(Am, ws.used));
+  }
+  return GCN_OK;
+}

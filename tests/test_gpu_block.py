@@ -14,7 +14,8 @@ from util import TOL_F32, check_bound, say
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(scope="module", params=[True, False], ids=["overlapped", "sequential"])
+@pytest.fixture(scope="module", params=[(True, "push"), (False, "push"), (True, "pull"), (False, "pull")],
+                ids=["overlapped", "sequential", "pull-overlapped", "pull-sequential"])
 def blk(request):
     import torch
     import bench
@@ -32,7 +33,7 @@ def blk(request):
     wtable.fill_table_torch(tab, w["table_seed"], dev)
     Ws = [torch.from_numpy(m).to(dev) for m in w["W"]]
     ep = bench.Epoch(gcn, torch, A, tab[lo:hi].to(dev), Ws, torch.from_numpy(w["y"]).to(dev), False, table=tab,
-                     overlap=request.param)
+                     overlap=request.param[0], backward=request.param[1])
     say(f"block epoch with halo gathers from the pinned host table, overlap={request.param}")
     ep.run()
     ep.run()
@@ -40,7 +41,7 @@ def blk(request):
     rng = np.random.default_rng(3)
     order = np.argsort(-og.deg.astype(np.int64), kind="stable")
     rows = np.unique(np.concatenate([order[:30], rng.integers(0, og.nr, 1200), [0, og.nr - 1]])).astype(np.int64)
-    return {"w": w, "og": og, "A": A, "ep": ep, "rows": rows, "tab": tab, "wtable": wtable}
+    return {"w": w, "og": og, "A": A, "ep": ep, "rows": rows, "tab": tab, "wtable": wtable, "pull": request.param[1] == "pull"}
 
 
 def test_block_arrays_and_halo_list_bit_exact(blk):
@@ -77,6 +78,8 @@ def test_block_forward_and_backward(blk):
     Z2 = ep.Zlast.cpu().numpy()
     loss, labs, G = oracle.softmax_xent(Z2, w["y"], 1.0 / og.nr)
     assert abs(float(ep.loss.item()) - loss) <= TOL_F32 * max(labs, np.abs(Z2).max() * 3)
+    if blk["pull"]:
+        return backward_pull_checks(blk, G, H0, H1)
     G2 = ep.G[1].cpu().numpy()
     onehot = np.zeros_like(G); onehot[np.arange(og.nr), w["y"]] = 1.0 / og.nr
     check_bound(G2, G, G + 2 * onehot, TOL_F32, "G2")
@@ -92,3 +95,24 @@ def test_block_forward_and_backward(blk):
     G1 = ep.G[0].cpu().numpy().astype(np.float64)
     AXf, BAXf = oracle.spmm(og.rowptr, og.col, og.val, H0)
     check_bound(ep.dW[0].cpu().numpy(), AXf.T @ G1, BAXf.T @ np.abs(G1), TOL_F32, "dW1")
+
+
+def backward_pull_checks(blk, G, H0, H1):
+    """Algorithm 2 on the block: halo rows of G^k from the table, T = A^ [G; G_halo], dH (owned rows, complete), dW."""
+    w, og, ep = blk["w"], blk["og"], blk["ep"]
+    W1, W2 = w["W"]
+    C = w["dims"][2]
+    want_halo = blk["wtable"].table_rows(og.halo_gid, w["dims"][0], w["table_seed"])
+    D2 = ep.D[1].cpu().numpy()
+    onehot = np.zeros_like(G); onehot[np.arange(og.nr), w["y"]] = 1.0 / og.nr
+    check_bound(D2[: og.nr], G, G + 2 * onehot, TOL_F32, "G2 (owned rows)")
+    assert np.array_equal(D2[og.nr:], want_halo[:, :C]), "halo rows of G2"
+    b2 = oracle.layer_bwd_pull(og, H1[: og.nr], W2, D2, Zprev=H1[: og.nr])
+    check_bound(ep.T[1].cpu().numpy(), b2["T"], b2["BT"], TOL_F32, "T2")
+    check_bound(ep.dW[1].cpu().numpy(), b2["dW"], b2["BdW"], TOL_F32, "dW2 (pull)")
+    D1 = ep.D[0].cpu().numpy()
+    check_bound(D1[: og.nr], b2["dH"], b2["BdH"], TOL_F32, "G1 (owned rows)")
+    assert np.array_equal(D1[og.nr:], want_halo), "halo rows of G1"
+    b1 = oracle.layer_bwd_pull(og, H0[: og.nr], W1, D1)
+    check_bound(ep.T[0].cpu().numpy(), b1["T"], b1["BT"], TOL_F32, "T1")
+    check_bound(ep.dW[0].cpu().numpy(), b1["dW"], b1["BdW"], TOL_F32, "dW1 (pull)")

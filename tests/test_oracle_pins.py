@@ -393,6 +393,38 @@ def test_layer_backward_on_blocks_sums_to_whole():
     np.testing.assert_allclose(S, bw["dH"], rtol=1e-11, atol=1e-12)
 
 
+def test_pull_backward_equals_gradient_on_symmetric_graph_and_adds_up_over_blocks():
+    """Algorithm 2 (pull form) on a symmetric A^: on the whole graph it must equal the push form, which the
+    finite differences above pin; on row blocks the dH rows are the whole graph's rows (complete, unlike the
+    push form) and the dW_m add up to dW."""
+    n, d_in, d_out = 80, 6, 4
+    src, dst = rand_edges(n, 300, 43)                    # undirected
+    whole = oracle.graph_build(src, dst, n)
+    assert np.array_equal(whole.rowptr, whole.colptr) and np.array_equal(whole.col, whole.rowidx)
+    rng = np.random.default_rng(5)
+    H = rng.standard_normal((n, d_in)).astype(np.float32)
+    W = rng.standard_normal((d_in, d_out)).astype(np.float32)
+    G = rng.standard_normal((n, d_out)).astype(np.float32)
+    Zp = rng.standard_normal((n, d_in)).astype(np.float32)
+    push = oracle.layer_bwd(whole, H, W, G, Zprev=Zp)
+    pull = oracle.layer_bwd_pull(whole, H, W, G, Zprev=Zp)
+    np.testing.assert_allclose(pull["dH"], push["dH"], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(pull["dW"], push["dW"], rtol=1e-11, atol=1e-12)
+    assert np.all(pull["dH"][Zp <= 0] == 0.0) and np.any(pull["dH"] != 0)
+    assert np.all(pull["BdH"] >= np.abs(pull["dH"])) and np.all(pull["BdW"] >= np.abs(pull["dW"]) - 1e-12)
+    dW = np.zeros((d_in, d_out))
+    for lo, hi in [(0, 25), (25, 26), (26, 80)]:
+        g = oracle.graph_build(src, dst, n, lo, hi, deg_global=whole.deg)
+        b = oracle.layer_bwd_pull(g, H[lo:hi], W, np.concatenate([G[lo:hi], G[g.halo_gid]]), Zprev=Zp[lo:hi])
+        np.testing.assert_allclose(b["dH"], push["dH"][lo:hi], rtol=1e-11, atol=1e-12)
+        dW += b["dW"]
+    np.testing.assert_allclose(dW, push["dW"], rtol=1e-11, atol=1e-12)
+    # on a directed graph the pull form is a different quantity (it multiplies by A^, the gradient by A^^T)
+    src, dst = rand_edges(n, 300, 44, directed=True)
+    gd = oracle.graph_build(src, dst, n)
+    assert np.abs(oracle.layer_bwd_pull(gd, H, W, G)["dH"] - oracle.layer_bwd(gd, H, W, G)["dH"]).max() > 1e-3
+
+
 def test_bias_and_identity_activation():
     n = 30
     src, dst = rand_edges(n, 100, 51)
