@@ -256,3 +256,42 @@ def train(g: Graph, X, Ws, y, lr, epochs, scale=None):
                 G = b["dH"][: g.nr].astype(np.float32)
         Ws = [sgd_update(Ws[k], dWs[k], lr) for k in range(L)]
     return losses, Ws
+
+
+def partition_stats(colptr, rowidx, rowptr, part, p):
+    """Communication figures of a 1D row partition under the column-net hypergraph model (Sec. 4.3.2): net n_j
+    joins the rows with a stored entry in column j; the part that owns vertex j sends row j once to every other
+    part of the net's connectivity set.  Plain loops over the nets, integers only.
+
+    part[i] in [0, p) for every vertex.  Returns a dict of
+      volume      sum_j (lambda(n_j) - 1): rows sent per sparse product (the paper's total, without its constant
+                  factors 2 and cost(n_j))
+      cut_entries stored entries (i, j) with part[i] != part[j] (what the graph model charges)
+      load[m]     sum of w(v_i) = stored entries in the rows of part m
+      send_rows[m], recv_rows[m]   rows part m sends / receives per product
+      send_msgs[m], recv_msgs[m]   number of parts it sends to / receives from
+    """
+    colptr = np.asarray(colptr, np.int64); rowidx = np.asarray(rowidx, np.int64)
+    rowptr = np.asarray(rowptr, np.int64); part = np.asarray(part, np.int64)
+    n = colptr.size - 1
+    assert part.size == n and rowptr.size == n + 1 and part.min(initial=0) >= 0 and part.max(initial=0) < p
+    send_rows = np.zeros(p, np.int64); recv_rows = np.zeros(p, np.int64)
+    pairs = set()
+    cut = 0
+    for j in range(n):
+        pins = rowidx[colptr[j]:colptr[j + 1]]
+        owner = int(part[j])
+        cut += int(np.count_nonzero(part[pins] != owner))
+        for q in set(part[pins].tolist()) - {owner}:          # connectivity set minus the owner
+            send_rows[owner] += 1
+            recv_rows[q] += 1
+            pairs.add((owner, q))
+    send_msgs = np.zeros(p, np.int64); recv_msgs = np.zeros(p, np.int64)
+    for m, q in pairs:
+        send_msgs[m] += 1
+        recv_msgs[q] += 1
+    load = np.zeros(p, np.int64)
+    for i in range(n):
+        load[part[i]] += rowptr[i + 1] - rowptr[i]
+    return {"volume": int(send_rows.sum()), "cut_entries": cut, "load": load, "send_rows": send_rows,
+            "recv_rows": recv_rows, "send_msgs": send_msgs, "recv_msgs": recv_msgs}

@@ -492,3 +492,77 @@ def test_training_loss_falls_on_a_small_graph():
     losses, _ = oracle.train(g, X, Ws, y, lr=0.5, epochs=25)
     assert all(b < a for a, b in zip(losses, losses[1:])), losses
     assert losses[-1] < losses[0] - 0.01          # labels are random: little can be learnt, but the loss must move
+
+
+# ----------------------------------------------------------------------------- partition statistics
+def _brute_stats(M, part, p):
+    """Dense 0/1 matrix, straight from the definitions: who needs row j, who owns it."""
+    n = M.shape[0]
+    need = np.zeros((p, n), bool)                         # need[q, j]: part q has a row with an entry in column j
+    for i in range(n):
+        for j in range(n):
+            if M[i, j]:
+                need[part[i], j] = True
+    send = np.zeros(p, int); recv = np.zeros(p, int); talk = np.zeros((p, p), bool)
+    for j in range(n):
+        for q in range(p):
+            if need[q, j] and q != part[j]:
+                send[part[j]] += 1; recv[q] += 1; talk[part[j], q] = True
+    return send, recv, talk.sum(1), talk.sum(0)
+
+
+def test_partition_stats_paper_example_and_brute_force():
+    f = _read_golden()
+    e = np.array([[int(x) for x in q.split("-")] for q in f["edges"]]) - 1
+    src = np.concatenate([e[:, 0], e[:, 1]]); dst = np.concatenate([e[:, 1], e[:, 0]])
+    g = oracle.graph_build(src, dst, 6)
+    part = np.zeros(6, int)
+    for m, q in enumerate(f["parts"]):
+        part[[int(x) - 1 for x in q.split(",")]] = m
+    st = oracle.partition_stats(g.colptr, g.rowidx, g.rowptr, part, 3)
+    # printed: lambda(n_2) = lambda(n_4) = 3, row 4 is transferred twice; processor 3 receives rows {1, 2} and {4}
+    lam = [len(set(part[g.rowidx[g.colptr[j]:g.colptr[j + 1]]].tolist())) for j in range(6)]
+    assert lam[1] == int(f["lambda_n2"][0]) and lam[3] == int(f["lambda_n4"][0])
+    assert st["volume"] == sum(lam) - 6
+    assert st["recv_rows"][2] == 3 and st["recv_msgs"][2] == 2
+    # part 2 owns v3 and v4; v3 has no neighbour outside its part, so all that part 2 sends is row 4, twice
+    assert st["send_rows"][1] == int(f["transfers_row4"][0]) and st["send_msgs"][1] == 2
+    cut_at_v4 = sum(1 for a, b in e if 3 in (a, b) and part[a] != part[b])
+    assert cut_at_v4 == int(f["cut_edges_at_v4"][0]) and lam[3] - 1 == int(f["transfers_row4"][0])
+    assert st["volume"] <= st["cut_entries"]                  # the graph model never undercounts
+    assert st["load"].tolist() == [int(g.deg[part == m].sum()) for m in range(3)]
+    # brute force from a dense matrix, directed graphs, uneven parts, an empty part
+    for seed, n, m, p in [(1, 17, 40, 4), (2, 30, 120, 5), (3, 9, 30, 9), (4, 25, 60, 1)]:
+        src, dst = rand_edges(n, m, seed, directed=True)
+        g = oracle.graph_build(src, dst, n)
+        rng = np.random.default_rng(seed)
+        part = rng.integers(0, max(p - 1, 1), n) if p > 2 else rng.integers(0, p, n)     # last part stays empty
+        M = csr_to_dense(g, g.val) != 0
+        st = oracle.partition_stats(g.colptr, g.rowidx, g.rowptr, part, p)
+        send, recv, smsg, rmsg = _brute_stats(M, part, p)
+        assert st["send_rows"].tolist() == send.tolist() and st["recv_rows"].tolist() == recv.tolist()
+        assert st["send_msgs"].tolist() == smsg.tolist() and st["recv_msgs"].tolist() == rmsg.tolist()
+        assert st["volume"] == send.sum() and st["cut_entries"] == sum(M[i, j] and part[i] != part[j] for i in range(n) for j in range(n))
+        assert st["load"].sum() == g.nnz
+    # one part: nothing moves; every vertex its own part: net j reaches deg_j parts
+    g = oracle.graph_build(*rand_edges(40, 150, 9), 40)
+    st = oracle.partition_stats(g.colptr, g.rowidx, g.rowptr, np.zeros(40, int), 1)
+    assert st["volume"] == 0 and st["send_msgs"].sum() == 0 and st["load"][0] == g.nnz
+    st = oracle.partition_stats(g.colptr, g.rowidx, g.rowptr, np.arange(40), 40)
+    assert st["volume"] == g.nnz - 40 and st["send_rows"].tolist() == (g.deg - 1).tolist()
+
+
+def test_partition_stats_agree_with_block_halo_lists():
+    """Contiguous parts: the rows a part receives are the halo list of its block build (pinned above)."""
+    n = 300
+    src, dst = rand_edges(n, 1500, 12, directed=True)
+    whole = oracle.graph_build(src, dst, n)
+    cuts = [0, 70, 71, 190, 300]
+    part = np.zeros(n, int)
+    for m in range(4):
+        part[cuts[m]:cuts[m + 1]] = m
+    st = oracle.partition_stats(whole.colptr, whole.rowidx, whole.rowptr, part, 4)
+    for m in range(4):
+        g = oracle.graph_build(src, dst, n, cuts[m], cuts[m + 1], deg_global=whole.deg)
+        assert st["recv_rows"][m] == g.nh and st["load"][m] == g.nnz
+        assert st["recv_msgs"][m] == len(set(part[g.halo_gid].tolist()))
