@@ -232,6 +232,26 @@ int gcn_layer_bwd_pull(const gcn_csr_t* A, int phase, const void* H, int64_t ldh
                        void* dH, void* stream);
 
 /*
+ * Communication figures of a 1D row partition, counted on the device (Sec. 4.3.2, the column-net hypergraph model
+ * and its total-volume formula; Sec. 5, the per-processor volume and message counts of the communication table).
+ * Net n_j joins the rows with a stored entry in column j; the part that owns vertex j sends row j once to every
+ * other part of the net's connectivity set.
+ *   A        handle of a whole graph (all rows, no halo columns).
+ *   d_part   device int32 [n]: part of every vertex, in [0, p);  1 <= p <= 32768.
+ * Results, device int64, each nullable:
+ *   d_load [p]       stored entries in the part's rows (sum of the vertex weights w(v_i) = |cols(A(i,:))|)
+ *   d_send_rows [p]  rows the part sends per sparse product;  d_recv_rows [p]  rows it receives (its halo size)
+ *   d_send_msgs [p]  parts it sends to;                       d_recv_msgs [p]  parts it receives from
+ *   d_totals [2]     { sum_j (lambda(n_j) - 1): all rows moved per product (the paper's total without the constant
+ *                      factors 2 and cost(n_j));  stored entries whose ends lie in different parts (what the graph
+ *                      model charges instead) }
+ * Integer work: exact.  Allocates temporaries (about 30 bytes per stored entry) and synchronises the stream.
+ */
+int gcn_partition_stats(const gcn_csr_t* A, const int32_t* d_part, int p, int64_t* d_load, int64_t* d_send_rows,
+                        int64_t* d_recv_rows, int64_t* d_send_msgs, int64_t* d_recv_msgs, int64_t* d_totals,
+                        void* stream);
+
+/*
  * Weight update of gradient descent (Sec. 3.1, last equation; last line of Algorithm 2):
  *   W <- W - lr * dW,   elementwise on n fp32 values (W and dW: device, contiguous, may not overlap).
  * One fused multiply-add per element.  Not part of the timed forward+backward epoch.

@@ -59,6 +59,8 @@ def _load():
     lib.gcn_dense_fwd.restype = C.c_int
     lib.gcn_layer_bwd_pull.argtypes = [vp, C.c_int, vp, C.c_int64, vp, C.c_int, C.c_int, C.c_int, vp, C.c_int64, vp, vp, vp, vp, vp, vp]
     lib.gcn_layer_bwd_pull.restype = C.c_int
+    lib.gcn_partition_stats.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp]
+    lib.gcn_partition_stats.restype = C.c_int
     lib.gcn_sgd_update.argtypes = [vp, vp, C.c_int64, C.c_float, vp]
     lib.gcn_sgd_update.restype = C.c_int
     lib.gcn_profile_enable.argtypes = [C.c_int]
@@ -344,6 +346,19 @@ def gcn_softmax_xent(Z: torch.Tensor, y: torch.Tensor, scale: float, loss: torch
     _check(_lib.gcn_softmax_xent(_ptr(Z), ldz, Z.shape[0], Cn, _dtype_code(Z), _ptr(y), float(scale), _ptr(loss),
                                  _ptr(G), ldg, _stream()), "gcn_softmax_xent")
     return loss
+
+
+def gcn_partition_stats(A: Csr, part: torch.Tensor, p: int):
+    """Returns a dict of int64 GPU tensors: load, send_rows, recv_rows, send_msgs, recv_msgs ([p] each), totals ([2])."""
+    _dev(part, torch.int32, "part")
+    if part.dim() != 1 or part.numel() != A.nr or not part.is_contiguous():
+        raise TypeError("gcn_partition_stats: part must be a contiguous int32 vector with one entry per vertex")
+    out = {k: torch.empty(2 if k == "totals" else max(int(p), 0), dtype=torch.int64, device=part.device)
+           for k in ("load", "send_rows", "recv_rows", "send_msgs", "recv_msgs", "totals")}
+    _check(_lib.gcn_partition_stats(A.handle, _ptr(part), int(p), _ptr(out["load"]), _ptr(out["send_rows"]),
+                                    _ptr(out["recv_rows"]), _ptr(out["send_msgs"]), _ptr(out["recv_msgs"]),
+                                    _ptr(out["totals"]), _stream()), "gcn_partition_stats")
+    return out
 
 
 def gcn_sgd_update(W: torch.Tensor, dW: torch.Tensor, lr: float):
