@@ -232,6 +232,23 @@ int gcn_layer_bwd_pull(const gcn_csr_t* A, int phase, const void* H, int64_t ldh
                        void* dH, void* stream);
 
 /*
+ * The subgraph induced by a vertex list, as a graph of its own (Sec. 4.3.3: a mini-batch is a subgraph
+ * G' = (V', E') of the input graph on which the convolutions run as in full-batch training).
+ *   A           handle of a whole graph (all rows, no halo columns).
+ *   d_vertices  device int32 [n_sub]: distinct vertex ids of A, in any order; vertex k of the result is d_vertices[k].
+ *   flags       GCN_BUILD_CSC or 0.
+ * Result: a new whole-graph handle on n_sub vertices whose stored entries are (a, b) for every stored entry
+ * (d_vertices[a], d_vertices[b]) of A, with degrees, diagonal and normalisation taken within the subgraph
+ * (A^' = D'^-1/2 (A' + I) D'^-1/2); arrays laid out as gcn_csr_build's.  Features and labels of the subgraph are
+ * the rows d_vertices of the parent's (gcn_halo_gather with d_vertices as the index list).  Integer arrays and
+ * values are bit-identical to building the relabelled edge list of G' with gcn_csr_build.
+ * Errors: an id outside the graph or listed twice gives GCN_EINVAL.  Allocates temporaries, synchronises the
+ * stream; free the result with gcn_csr_free.
+ */
+int gcn_csr_induced(const gcn_csr_t* A, const int32_t* d_vertices, int64_t n_sub, int flags, void* stream,
+                    gcn_csr_t** out);
+
+/*
  * Communication figures of a 1D row partition, counted on the device (Sec. 4.3.2, the column-net hypergraph model
  * and its total-volume formula; Sec. 5, the per-processor volume and message counts of the communication table).
  * Net n_j joins the rows with a stored entry in column j; the part that owns vertex j sends row j once to every

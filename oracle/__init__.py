@@ -295,3 +295,15 @@ def partition_stats(colptr, rowidx, rowptr, part, p):
         load[part[i]] += rowptr[i + 1] - rowptr[i]
     return {"volume": int(send_rows.sum()), "cut_entries": cut, "load": load, "send_rows": send_rows,
             "recv_rows": recv_rows, "send_msgs": send_msgs, "recv_msgs": recv_msgs}
+
+
+def induced_edges(src, dst, n, vertices):
+    """Edge list of the subgraph induced by a vertex list, in the subgraph's numbering (Sec. 4.3.3: a mini-batch
+    is G' = (V', E'), V' a subset of V and E' the edges of E between vertices of V'): vertex k of G' is
+    vertices[k].  graph_build on the result gives the subgraph's own normalised adjacency."""
+    src = np.asarray(src, np.int64); dst = np.asarray(dst, np.int64); vertices = np.asarray(vertices, np.int64)
+    assert np.unique(vertices).size == vertices.size and vertices.min() >= 0 and vertices.max() < n
+    number = np.full(n, -1, np.int64)
+    number[vertices] = np.arange(vertices.size)
+    keep = (number[src] >= 0) & (number[dst] >= 0)
+    return number[src[keep]].astype(np.int32), number[dst[keep]].astype(np.int32)

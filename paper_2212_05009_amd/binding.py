@@ -61,6 +61,8 @@ def _load():
     lib.gcn_layer_bwd_pull.restype = C.c_int
     lib.gcn_partition_stats.argtypes = [vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp]
     lib.gcn_partition_stats.restype = C.c_int
+    lib.gcn_csr_induced.argtypes = [vp, vp, C.c_int64, C.c_int, vp, C.POINTER(C.c_void_p)]
+    lib.gcn_csr_induced.restype = C.c_int
     lib.gcn_sgd_update.argtypes = [vp, vp, C.c_int64, C.c_float, vp]
     lib.gcn_sgd_update.restype = C.c_int
     lib.gcn_profile_enable.argtypes = [C.c_int]
@@ -189,6 +191,17 @@ def gcn_csr_build(src: torch.Tensor, dst: torch.Tensor, n_global: int, row_lo: i
                                 _stream(), C.byref(out))
     _check(rc, "gcn_csr_build")
     return Csr(out, src.device)
+
+
+def gcn_csr_induced(A: Csr, vertices: torch.Tensor, flags: int = BUILD_CSC) -> Csr:
+    _dev(vertices, torch.int32, "vertices")
+    if vertices.dim() != 1 or not vertices.is_contiguous():
+        raise TypeError("vertices must be a contiguous int32 vector")
+    out = C.c_void_p()
+    with torch.cuda.device(vertices.device):
+        rc = _lib.gcn_csr_induced(A.handle, _ptr(vertices), vertices.numel(), flags, _stream(), C.byref(out))
+    _check(rc, "gcn_csr_induced")
+    return Csr(out, vertices.device)
 
 
 def gcn_spmm(A: Csr, X: torch.Tensor, Y: torch.Tensor, epilogue: int = EPI_NONE, bias: torch.Tensor | None = None,

@@ -566,3 +566,32 @@ def test_partition_stats_agree_with_block_halo_lists():
         g = oracle.graph_build(src, dst, n, cuts[m], cuts[m + 1], deg_global=whole.deg)
         assert st["recv_rows"][m] == g.nh and st["load"][m] == g.nnz
         assert st["recv_msgs"][m] == len(set(part[g.halo_gid].tolist()))
+
+
+# ----------------------------------------------------------------------------- induced subgraphs
+def test_induced_subgraph_is_the_dense_submatrix():
+    """Sec. 4.3.3: the mini-batch graph has the edges between selected vertices; checked entry by entry against
+    the dense pattern restricted to the selection, with the normalisation recomputed from its own row sums."""
+    for seed, n, m, k, directed in [(1, 40, 200, 13, True), (2, 60, 500, 60, False), (3, 25, 90, 1, True), (4, 30, 0, 7, False)]:
+        src, dst = rand_edges(n, m, seed, directed=directed) if m else (np.zeros(0, np.int32), np.zeros(0, np.int32))
+        P = np.zeros((n, n), bool)
+        P[src, dst] = True
+        np.fill_diagonal(P, False)
+        rng = np.random.default_rng(seed)
+        V = rng.permutation(n)[:k]
+        s2, d2 = oracle.induced_edges(src, dst, n, V)
+        g = oracle.graph_build(s2, d2, k)
+        sub = P[np.ix_(V, V)] | np.eye(k, dtype=bool)
+        deg = sub.sum(1)
+        want = np.where(sub, 1.0 / np.sqrt(np.outer(deg, deg)), 0.0)
+        got = csr_to_dense(g, g.val64)
+        assert np.array_equal(got != 0, sub) and np.array_equal(g.deg, deg)
+        np.testing.assert_allclose(got, want, rtol=1e-14)
+    # every vertex in its own order: the graph itself; a permutation: the symmetric permutation of A^
+    src, dst = rand_edges(35, 150, 8, directed=True)
+    whole = oracle.graph_build(src, dst, 35)
+    same = oracle.graph_build(*oracle.induced_edges(src, dst, 35, np.arange(35)), 35)
+    assert np.array_equal(same.col, whole.col) and np.array_equal(same.val, whole.val)
+    perm = np.random.default_rng(0).permutation(35)
+    gp = oracle.graph_build(*oracle.induced_edges(src, dst, 35, perm), 35)
+    assert np.array_equal(csr_to_dense(gp, gp.val), csr_to_dense(whole, whole.val)[np.ix_(perm, perm)])
