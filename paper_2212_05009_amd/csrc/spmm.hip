@@ -4,7 +4,7 @@
 // that its cost is proportional to the row's entry count, so rows are binned by length:
 //   * ordinary rows: the 64 lanes of a wavefront form G = 64 / LPR groups of LPR lanes; a group
 //     covers (a slice of) the feature dimension with V-wide vector loads, so one gathered feature
-//     row is one coalesced request.  Rows of a length class of about 4*g entries are shared by g
+//     row is one coalesced request.  Rows of a length class of about 32*g entries are shared by g
 //     groups (g = 1 .. G), so a wavefront takes G / g rows at once: short rows do not idle lanes,
 //     long rows get all groups; a butterfly over the g groups finishes a row.
 //   * hub rows (more than kHubRowNnz entries): cut into chunks of kHubChunkNnz entries, one

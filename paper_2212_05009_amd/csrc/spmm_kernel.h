@@ -1,5 +1,7 @@
 // Device templates of the sparse-times-dense kernels (included by spmm.hip, spmm_f32.hip, spmm_bf16.hip).
 #pragma once
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace gcn {
@@ -330,8 +332,11 @@ __global__ __launch_bounds__(256) void k_spmm_hub_finish(SpmmK a) {
 
 struct SpmmProf { int kind; int dtype; int64_t rows, nnz; double alg, touched, flops; };
 
-// Entries each lane group should get before a row is shared by more groups.
-constexpr int kEntriesPerGroup = 4;
+// Entries each lane group should get before a row is shared by more groups (GCN_SPMM_EPG overrides, for
+// experiments).  Measured on an R-MAT graph with 45 entries per row: 4 / 8 / 16 / 32 / 64 entries per group
+// give 460 / 441 / 431 / 427 / 427 us at width 128 and 122 / 113 / 108 / 107 / 110 us at width 16: a
+// wavefront that holds more rows keeps more gathers in flight per round trip of its dependent loads.
+constexpr int kEntriesPerGroup = 32;
 
 static inline int pow2_ceil_i(int x) { int p = 1; while (p < x) p <<= 1; return p; }
 
@@ -345,7 +350,9 @@ static int launch_l(SpmmK& k, const Schedule* sc, const SpmmProf& pf, bool narro
     const int64_t cnt = sc->class_begin[c + 1] - sc->class_begin[c];
     if (cnt <= 0) continue;
     const int64_t len_hi = c >= 32 ? 0 : ((int64_t)1 << (32 - c)) - 1;
-    const int64_t want = ceil_div(len_hi > 0 ? len_hi : 1, kEntriesPerGroup);
+    static const int epg_env = [] { const char* e = getenv("GCN_SPMM_EPG"); return e ? atoi(e) : 0; }();
+    const int epg = epg_env > 0 ? epg_env : kEntriesPerGroup;
+    const int64_t want = ceil_div(len_hi > 0 ? len_hi : 1, epg);
     int groups = pow2_ceil_i((int)(want < G ? want : G));
     if (groups > G) groups = G;
     int lg = 0; while ((1 << lg) < groups) ++lg;
