@@ -13,6 +13,8 @@
 //               (c = l%32, h = l/32) loads A[k + h][m0 + c] and B[k + h][n0 + c]: 128-byte coalesced
 //               rows.  The four wavefronts of a block take interleaved row chunks of one output tile,
 //               add their tiles through LDS and write one partial tile per block.
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace gcn {
@@ -203,6 +205,162 @@ __global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <
   }
 }
 
+// ---- the same product without a single data-dependent branch ----------------------------------------
+// For operands whose rows are 16-byte aligned, K = 16 KU with KU = 1, 2, 4 (the whole row in one request)
+// or a multiple of 128 (KU = 8), N a multiple of 16 and a mask that covers every row.  Every load is an
+// unconditional 16-byte (bf16: 8-byte) request - rows beyond M are clamped to the last row and dropped at
+// the store - so the compiler can keep the next step's operand loads in flight across the MFMAs of the
+// current one instead of waiting at every join of the general kernel's bounds checks.
+template <typename T> __device__ __forceinline__ void vload4(const T* __restrict__ p, float (&o)[4]) {
+  if constexpr (sizeof(T) == 4) {
+    const floatx4 v = *reinterpret_cast<const floatx4*>(p);
+    o[0] = v[0]; o[1] = v[1]; o[2] = v[2]; o[3] = v[3];
+  } else {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 v = *reinterpret_cast<const u32x2*>(p);
+    o[0] = __uint_as_float(v[0] << 16); o[1] = __uint_as_float(v[0] & 0xffff0000u);
+    o[2] = __uint_as_float(v[1] << 16); o[3] = __uint_as_float(v[1] & 0xffff0000u);
+  }
+}
+template <typename T> __device__ __forceinline__ void vstore4(T* __restrict__ p, const float (&v)[4]) {
+  if constexpr (sizeof(T) == 4) {
+    *reinterpret_cast<floatx4*>(p) = floatx4{v[0], v[1], v[2], v[3]};
+  } else {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    bf16_t h[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) stg<T>(&h[i], v[i]);
+    *reinterpret_cast<u32x2*>(p) = u32x2{(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
+  }
+}
+
+template <typename T, int NT, int KU, bool MASK, bool SAVE>
+__global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <= 8 ? 4 : 2, 8))) void k_gemm_nn_fast(NnDirectArgs a) {
+  // W in LDS.  NT a multiple of 4: [k][t / 4][c][t % 4], so that the four column tiles 4 tq .. 4 tq + 3 of a
+  // lane's (k, c) are one 16-byte read and the 16 lanes of a k row read 256 contiguous bytes.  Else [k][LDW].
+  extern __shared__ float Ws[];
+  constexpr int LDW = NT * 16 + 4;
+  constexpr bool kQuad = NT % 4 == 0;
+  constexpr int TQ = kQuad ? NT / 4 : 1;
+  for (int e = threadIdx.x; e < a.K * NT * 16; e += kNnThreads) {
+    const int k = e / (NT * 16), n = e % (NT * 16);
+    const int t = n >> 4, cc = n & 15;
+    const int at = kQuad ? ((k * TQ + (t >> 2)) * 16 + cc) * 4 + (t & 3) : k * LDW + n;
+    Ws[at] = a.W[(int64_t)k * a.ldw + n];
+  }
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = lane & 15, q = lane >> 4;
+  const T* __restrict__ A = reinterpret_cast<const T*>(a.A);
+  T* __restrict__ C = reinterpret_cast<T*>(a.C);
+  T* __restrict__ C2 = reinterpret_cast<T*>(a.C2);
+  const T* __restrict__ Mk = reinterpret_cast<const T*>(a.mask);
+  constexpr int WPB = kNnThreads / 64;
+  const int64_t ntiles = (a.M + 15) / 16;
+  const int64_t stride = (int64_t)gridDim.x * WPB;
+  const int chunks = a.K / (16 * KU);                 // k chunks per tile
+  // mask values of the next tile travel with its operand rows when a tile is a single chunk and they fit
+  constexpr bool kPrefetchMask = MASK && KU <= 2 && NT <= 8;
+
+  auto load_a = [&](int64_t tile, int chunk, float (&av)[KU][4]) {
+    const int64_t row = tile * 16 + c;
+    const T* __restrict__ arow = A + (row < a.M ? row : a.M - 1) * a.lda + chunk * (16 * KU) + 4 * q;
+#pragma unroll
+    for (int u = 0; u < KU; ++u) vload4<T>(arow + 16 * u, av[u]);
+  };
+  auto load_m = [&](int64_t tile, float (&keep)[NT][4]) {
+    const int64_t row = tile * 16 + c;
+    const T* __restrict__ mrow = Mk + (row < a.M ? row : a.M - 1) * a.ldmask + 4 * q;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) vload4<T>(mrow + 16 * t, keep[t]);
+  };
+
+  int64_t tile = (int64_t)blockIdx.x * WPB + w;
+  if (tile >= ntiles) return;
+  float a_nxt[KU][4];
+  float m_nxt[kPrefetchMask ? NT : 1][4];
+  load_a(tile, 0, a_nxt);
+  if constexpr (kPrefetchMask) load_m(tile, m_nxt);
+  for (; tile < ntiles; tile += stride) {
+    floatx4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float keep[kPrefetchMask ? NT : 1][4];
+    if constexpr (kPrefetchMask) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) keep[t][i] = m_nxt[t][i];
+    }
+    for (int chunk = 0; chunk < chunks; ++chunk) {
+      float av[KU][4];
+#pragma unroll
+      for (int u = 0; u < KU; ++u)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) av[u][i] = a_nxt[u][i];
+      // the next request: this tile's next chunk, else the first chunk of the wavefront's next tile
+      // (clamped to the last tile: a valid, wasted load at the very end)
+      const bool same = chunk + 1 < chunks;
+      const int64_t nt = same ? tile : (tile + stride < ntiles ? tile + stride : ntiles - 1);
+      load_a(nt, same ? chunk + 1 : 0, a_nxt);
+      if constexpr (kPrefetchMask) load_m(nt, m_nxt);
+      if constexpr (kQuad) {
+        // the W operands of step (u, i + 1) are read from LDS before the MFMAs of step (u, i) are issued
+        const floatx4* wq = reinterpret_cast<const floatx4*>(Ws) + ((chunk * (16 * KU) + 4 * q) * TQ) * 16 + c;
+        floatx4 wc[TQ], wn[TQ];
+#pragma unroll
+        for (int tq = 0; tq < TQ; ++tq) wc[tq] = wq[tq * 16];
+#pragma unroll
+        for (int st = 0; st < KU * 4; ++st) {
+          const int u = st >> 2, i = st & 3;
+          if (st + 1 < KU * 4) {
+            const int kn = 16 * ((st + 1) >> 2) + ((st + 1) & 3);
+#pragma unroll
+            for (int tq = 0; tq < TQ; ++tq) wn[tq] = wq[(kn * TQ + tq) * 16];
+          }
+#pragma unroll
+          for (int tq = 0; tq < TQ; ++tq)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              acc[tq * 4 + r] = __builtin_amdgcn_mfma_f32_16x16x4f32(wc[tq][r], av[u][i], acc[tq * 4 + r], 0, 0, 0);
+#pragma unroll
+          for (int tq = 0; tq < TQ; ++tq) wc[tq] = wn[tq];
+        }
+      } else {
+        const float* wbase = Ws + (chunk * (16 * KU) + 4 * q) * LDW + c;
+#pragma unroll
+        for (int u = 0; u < KU; ++u)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float* wrow = wbase + (16 * u + i) * LDW;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+              acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(wrow[t * 16], av[u][i], acc[t], 0, 0, 0);
+          }
+      }
+    }
+    // register r of lane (c, q) holds output column 16t + 4q + r of row c
+    const int64_t m = tile * 16 + c;
+    if (m < a.M) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const int n = t * 16 + 4 * q;
+        float v[4], pre[4], kp[4];
+        if constexpr (MASK && !kPrefetchMask) vload4<T>(Mk + m * a.ldmask + n, kp);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          pre[r] = acc[t][r] + (a.bias ? a.bias[n + r] : 0.f);
+          v[r] = a.relu ? (pre[r] > 0.f ? pre[r] : 0.f) : pre[r];
+          if constexpr (MASK) v[r] = (kPrefetchMask ? keep[t][r] : kp[r]) > 0.f ? v[r] : 0.f;
+        }
+        if constexpr (SAVE) vstore4<T>(C2 + m * a.ldc2 + n, pre);
+        vstore4<T>(C + m * a.ldc + n, v);
+      }
+    }
+  }
+}
+
 static int nn_tiles(int N) { return N <= 16 ? 1 : N <= 32 ? 2 : N <= 48 ? 3 : N <= 64 ? 4 : N <= 128 ? 8 : 16; }
 
 size_t gemm_nn_direct_lds_bytes(int N, int K) {
@@ -225,8 +383,53 @@ static int nn_launch(const NnDirectArgs& a, hipStream_t s) {
   return GCN_OK;
 }
 
+template <typename T, int NT, int KU>
+static int nn_launch_fast(const NnDirectArgs& a, hipStream_t s) {
+  const size_t lds = gemm_nn_direct_lds_bytes(a.N, a.K);
+  const int64_t ntiles = ceil_div(a.M, 16);
+  const int per_cu = lds > 80 * 1024 ? 1 : 2;
+  int64_t blocks = ceil_div(ntiles, kNnThreads / 64);
+  if (blocks > 256 * per_cu) blocks = 256 * per_cu;
+  auto go = [&](auto kern) -> int {
+    GCN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    kern<<<dim3((unsigned)blocks), dim3(kNnThreads), lds, s>>>(a);
+    GCN_CHECK_LAUNCH();
+    return GCN_OK;
+  };
+  if (a.mask) return go(k_gemm_nn_fast<T, NT, KU, true, false>);
+  return a.C2 ? go(k_gemm_nn_fast<T, NT, KU, false, true>) : go(k_gemm_nn_fast<T, NT, KU, false, false>);
+}
+
+// the branch-free kernel serves the layer shapes (N = 16 NT, K = 16, 32, 64 or a multiple of 128, aligned rows)
+template <typename T>
+static bool nn_fast(const NnDirectArgs& a, hipStream_t s, int* rc) {
+  static const bool off = getenv("GCN_GEMM_FAST") && atoi(getenv("GCN_GEMM_FAST")) == 0;
+  const int NT = nn_tiles(a.N);
+  if (off || a.N != NT * 16 || a.vecA != 4 || a.vecC != 4 || (a.C2 && a.vecC2 != 4)) return false;
+  if (a.mask && (a.vecM != 4 || a.mask_rows < a.M || a.C2)) return false;
+  const int ku = a.K % 128 == 0 ? 8 : a.K == 64 ? 4 : a.K == 32 ? 2 : a.K == 16 ? 1 : 0;
+  if (ku == 0) return false;
+#define GCN_NN_FAST(NTV)                                              \
+  {                                                                   \
+    *rc = ku == 1 ? nn_launch_fast<T, NTV, 1>(a, s) : ku == 2 ? nn_launch_fast<T, NTV, 2>(a, s) \
+        : ku == 4 ? nn_launch_fast<T, NTV, 4>(a, s) : nn_launch_fast<T, NTV, 8>(a, s);          \
+    return true;                                                      \
+  }
+  switch (NT) {
+    case 1: GCN_NN_FAST(1)
+    case 2: GCN_NN_FAST(2)
+    case 3: GCN_NN_FAST(3)
+    case 4: GCN_NN_FAST(4)
+    case 8: GCN_NN_FAST(8)
+    default: GCN_NN_FAST(16)
+  }
+#undef GCN_NN_FAST
+}
+
 template <typename T>
 static int nn_dispatch(const NnDirectArgs& a, hipStream_t s) {
+  int rc = GCN_OK;
+  if (nn_fast<T>(a, s, &rc)) return rc;
   switch (nn_tiles(a.N)) {
     case 1: return nn_launch<T, 1>(a, s);
     case 2: return nn_launch<T, 2>(a, s);
