@@ -408,8 +408,15 @@ __global__ __launch_bounds__(256) void k_tn_reduce(const float* __restrict__ par
   const int el = threadIdx.x & 15, r = threadIdx.x >> 4;
   const int64_t e = (int64_t)blockIdx.x * 16 + el;
   double s = 0.0;
-  if (e < mn)
-    for (int p = r; p < nsplit; p += 16) s += (double)partial[(int64_t)p * mn + e];
+  if (e < mn) {
+    int p = r;
+    for (; p + 48 < nsplit; p += 64) {          // four loads in flight, added in split order
+      const float v0 = partial[(int64_t)p * mn + e], v1 = partial[(int64_t)(p + 16) * mn + e];
+      const float v2 = partial[(int64_t)(p + 32) * mn + e], v3 = partial[(int64_t)(p + 48) * mn + e];
+      s += (double)v0; s += (double)v1; s += (double)v2; s += (double)v3;
+    }
+    for (; p < nsplit; p += 16) s += (double)partial[(int64_t)p * mn + e];
+  }
   red[r][el] = s;
   __syncthreads();
   if (r == 0 && e < mn) {

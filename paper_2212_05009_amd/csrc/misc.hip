@@ -135,7 +135,7 @@ static int gather_v(const char* table, int64_t ldb, int64_t nt, int n_vec, const
 // last layer): one group of LPR lanes per row.  The loss terms are added in fp64: per thread,
 // then per block in a fixed tree, then over the blocks in block order.
 // ------------------------------------------------------------------------------------------
-constexpr int kLossBlocks = 2048;
+constexpr int kLossBlocks = 4096;
 __device__ double g_loss_partial[kLossBlocks];
 
 template <typename T> __device__ __forceinline__ float ldf(const T* p) {
@@ -178,6 +178,10 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, i
 #pragma unroll
       for (int off = 1; off < LPR; off <<= 1) se += __shfl_xor(se, off, 64);
       if (in) stf<T>(go + l, scale * (ev * (1.0f / se) - (l == label ? 1.f : 0.f)));
+      // the label's logit sits in lane `label` of this row's lane group: no second, dependent load
+      const float zl = __shfl(zv, g * LPR + label, 64);
+      if (l == 0) local += (double)(mx + logf(se)) - (double)zl;
+      continue;
     } else {
       for (int c = l; c < C; c += LPR) mx = fmaxf(mx, ldf<T>(z + c));
 #pragma unroll
@@ -208,7 +212,12 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, i
 __global__ __launch_bounds__(256) void k_loss_finish(int nblocks, float scale, float* __restrict__ loss) {
   __shared__ double red[256];
   double s = 0.0;
-  for (int b = threadIdx.x; b < nblocks; b += 256) s += g_loss_partial[b];
+  int b = threadIdx.x;
+  for (; b + 768 < nblocks; b += 1024) {           // four loads in flight, added in block order
+    const double v0 = g_loss_partial[b], v1 = g_loss_partial[b + 256], v2 = g_loss_partial[b + 512], v3 = g_loss_partial[b + 768];
+    s += v0; s += v1; s += v2; s += v3;
+  }
+  for (; b < nblocks; b += 256) s += g_loss_partial[b];
   red[threadIdx.x] = s;
   __syncthreads();
   for (int off = 128; off > 0; off >>= 1) {

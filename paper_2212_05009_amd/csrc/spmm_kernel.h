@@ -325,8 +325,17 @@ __global__ __launch_bounds__(256) void k_spmm_hub_finish(SpmmK a) {
   if (f >= a.d) return;
   const int64_t row = a.hub_rows[h];
   const int64_t c_lo = a.hub_chunk_ptr[h], c_hi = a.hub_chunk_ptr[h + 1];
+  // chunk order, eight loads in flight at a time (a hub of a power-law graph has dozens of chunks)
   float v = 0.f;
-  for (int64_t c = c_lo; c < c_hi; ++c) v += a.partial[c * a.d + f];
+  int64_t c = c_lo;
+  for (; c + 8 <= c_hi; c += 8) {
+    float p[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) p[u] = a.partial[(c + u) * a.d + f];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v += p[u];
+  }
+  for (; c < c_hi; ++c) v += a.partial[c * a.d + f];
   finish_element<T>(a, row, f, v);
 }
 
