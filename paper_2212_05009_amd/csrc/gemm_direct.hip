@@ -15,6 +15,8 @@
 //               add their tiles through LDS and write one partial tile per block.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "common.h"
 
 namespace gcn {
@@ -570,6 +572,191 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
     }
 }
 
+// ---- the same contraction with vector requests ------------------------------------------------------------
+// The texture path takes as long for a 4-byte request per lane as for a 16-byte one, and the kernel above
+// issues one 4-byte request per MFMA: it is bound by that path, not by the matrix pipe or by memory.  Here a
+// lane asks for 4 consecutive columns of A at once (and TN consecutive columns of B): component i of the
+// request is the lane's operand for column tile i, so tile i holds the columns {4 c + i} and the 32 lanes of a
+// row half read 512 contiguous bytes.  The MFMA never sees the permutation; it is undone when the partial tile
+// is stored.  One request per four (TN = 1) or four requests per sixteen (TN = 2) MFMAs.  The next chunk's
+// requests are issued before the MFMAs of the current one; scheduling barriers keep them there.
+// Needs rows of A aligned to 4 elements and, for TN = 2, rows of B aligned to 2.
+template <typename T, int N> struct RawVec;
+template <> struct RawVec<float, 4> { typedef floatx4 type; };
+template <> struct RawVec<float, 2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct RawVec<float, 1> { typedef float type; };
+template <> struct RawVec<bf16_t, 4> { typedef uint32_t type __attribute__((ext_vector_type(2))); };
+template <> struct RawVec<bf16_t, 2> { typedef uint32_t type; };
+template <> struct RawVec<bf16_t, 1> { typedef uint16_t type; };
+
+template <typename T, int N>
+__device__ __forceinline__ void raw_to_f32(const typename RawVec<T, N>::type& v, uint32_t (&o)[N]) {
+  if constexpr (sizeof(T) == 4) {
+    if constexpr (N == 1) o[0] = __float_as_uint(v);
+    else {
+#pragma unroll
+      for (int i = 0; i < N; ++i) o[i] = __float_as_uint(v[i]);
+    }
+  } else {
+    if constexpr (N == 1) o[0] = (uint32_t)v << 16;
+    else if constexpr (N == 2) { o[0] = v << 16; o[1] = v & 0xffff0000u; }
+    else { o[0] = v[0] << 16; o[1] = v[0] & 0xffff0000u; o[2] = v[1] << 16; o[3] = v[1] & 0xffff0000u; }
+  }
+}
+
+template <typename T, int TN, int UK, int WN>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 8))) void k_gemm_tn_wide(TnDirectArgs a) {
+  // the four wavefronts of a block: WN column tiles of B side by side (all of them read the same rows of A,
+  // which then come from HBM once) times WK = 4 / WN interleaved sets of row chunks, added up at the end
+  constexpr int TM = 4, CH = 2 * UK, WK = 4 / WN;
+  typedef typename RawVec<T, TM>::type AV;
+  typedef typename RawVec<T, TN>::type BV;
+  __shared__ float red[2][TM * TN * 16 * 64];
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int c = lane & 31, h = lane >> 5;
+  const int wn = w % WN, kw = w / WN;
+  const int m0 = blockIdx.y * (32 * TM), n0 = (blockIdx.z * WN + wn) * (32 * TN);
+  const int64_t k_lo = (int64_t)blockIdx.x * a.rows_per_split;
+  const int64_t k_hi = k_lo + a.rows_per_split < a.Kd ? k_lo + a.rows_per_split : a.Kd;
+  const T* __restrict__ A = reinterpret_cast<const T*>(a.A);
+  const T* __restrict__ B = reinterpret_cast<const T*>(a.B);
+
+  // the lane's columns; a request that starts past the operand is moved to column 0 and cleared
+  const int ma = m0 + TM * c, nb = n0 + TN * c;
+  uint32_t amask[TM], bmask[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) amask[i] = ma + i < a.M ? 0xffffffffu : 0u;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bmask[j] = nb + j < a.N ? 0xffffffffu : 0u;
+  // a request is (row pair, uniform over the wavefront) + (lane half and column, 32 bits per lane).  Where the
+  // split ends on the first row of a pair both lane halves read that row, and a pair past the end reads the
+  // first rows of the split; what is not part of the product is cleared when the values are used.
+  const bool two_rows = k_lo + 1 < k_hi;
+  const uint32_t acol = (uint32_t)((ma < a.M ? ma : 0) * (int64_t)sizeof(T));      // bytes
+  const uint32_t bcol = (uint32_t)((nb < a.N ? nb : 0) * (int64_t)sizeof(T));
+  const uint32_t aoff = acol + (uint32_t)(h * a.lda * (int64_t)sizeof(T));
+  const uint32_t boff = bcol + (uint32_t)(h * a.ldb * (int64_t)sizeof(T));
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  auto load = [&](int64_t k, AV (&av)[UK], BV (&bv)[UK]) {
+#pragma unroll
+    for (int u = 0; u < UK; ++u) {
+      const int64_t kp = k + 2 * u;
+      const int64_t kc = kp < k_hi ? kp : k_lo;
+      const bool both = kp + 1 < k_hi || (kp >= k_hi && two_rows);          // rows kc and kc + 1 both lie in the split
+      av[u] = *reinterpret_cast<const AV*>(reinterpret_cast<const char*>(A + kc * a.lda) + (both ? aoff : acol));
+      bv[u] = *reinterpret_cast<const BV*>(reinterpret_cast<const char*>(B + kc * a.ldb) + (both ? boff : bcol));
+    }
+  };
+  int64_t k = k_lo + (int64_t)kw * CH;
+  AV an[UK]; BV bn[UK];
+  if (k < k_hi) load(k, an, bn);
+  for (; k < k_hi; k += WK * CH) {
+    float av[UK][TM], bv[UK][TN];
+#pragma unroll
+    for (int u = 0; u < UK; ++u) {
+      const uint32_t rmask = k + 2 * u + h < k_hi ? 0xffffffffu : 0u;   // cleared by a bit mask, never by a branch
+      uint32_t ra[TM], rb[TN];
+      raw_to_f32<T, TM>(an[u], ra);
+      raw_to_f32<T, TN>(bn[u], rb);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) av[u][i] = __uint_as_float(ra[i] & (amask[i] & rmask));
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bv[u][j] = __uint_as_float(rb[j] & (bmask[j] & rmask));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const int64_t kn = k + WK * CH;
+    load(kn < k_hi ? kn : k, an, bn);                      // past the end: the current chunk again, unused
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < UK; ++u)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[u][i], bv[u][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  // add up the row sets of a column tile
+  auto dump = [&](float* buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) buf[((i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+  };
+  auto take = [&](const float* buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] += buf[((i * TN + j) * 16 + r) * 64 + lane];
+  };
+  if constexpr (WK == 4) {               // (2, 3) -> LDS -> (0, 1) add; 1 -> LDS -> 0 adds
+    if (kw >= 2) dump(red[kw - 2]);
+    __syncthreads();
+    if (kw < 2) take(red[kw]);
+    __syncthreads();
+    if (kw == 1) dump(red[0]);
+    __syncthreads();
+    if (kw != 0) return;
+    take(red[0]);
+  } else if constexpr (WK == 2) {        // the second row set of each column tile -> LDS -> the first adds
+    if (kw == 1) dump(red[wn]);
+    __syncthreads();
+    if (kw != 0) return;
+    take(red[wn]);
+  }
+  // register r of lane (c, h) holds the product of A's lane 8 (r / 4) + 4 h + r % 4 and B's lane c
+  float* __restrict__ P = a.partial + (int64_t)blockIdx.x * a.M * a.N;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = nb + j;
+      if (n >= a.N) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + TM * (8 * (r / 4) + 4 * h + (r % 4)) + i;
+        if (m < a.M) P[(int64_t)m * a.N + n] = acc[i][j][r];
+      }
+    }
+}
+
+constexpr int kWideUK1 = 8, kWideUK2 = 8;   // row pairs per request batch (TN = 1, TN = 2)
+
+static bool tn_wide_ok(const void* A, int64_t lda, const void* B, int64_t ldb, int N, int dtype) {
+  static const bool off = getenv("GCN_GEMM_TN_WIDE") && atoi(getenv("GCN_GEMM_TN_WIDE")) == 0;
+  const size_t es = dtype == GCN_BF16 ? 2 : 4;
+  if (off || (lda % 4) != 0 || ((uintptr_t)A % (4 * es)) != 0) return false;
+  if (N > 32 && ((ldb % 2) != 0 || ((uintptr_t)B % (2 * es)) != 0)) return false;
+  return true;
+}
+
+// column tiles of B per block in the vector variant: all of B for up to 256 columns
+static int tn_wide_wn(int N) { return N <= 64 ? 1 : N <= 128 ? 2 : 4; }
+
+// splits of the vector variant: about two blocks per compute unit
+static int tn_wide_splits(int64_t Kd, int M, int N) {
+  static const int blocks = [] { const char* e = getenv("GCN_GEMM_TN_BLOCKS"); const int v = e ? atoi(e) : 0; return v > 0 ? v : 512; }();
+  const int64_t tiles = ceil_div(M, 128) * ceil_div(N, (N <= 32 ? 32 : 64) * tn_wide_wn(N));
+  int64_t want = ceil_div(blocks, tiles);
+  int64_t max_by_k = ceil_div(Kd, 512);
+  int64_t ns = want < max_by_k ? want : max_by_k;
+  return (int)(ns < 1 ? 1 : ns);
+}
+
 static int tn_direct_tn(int N) { return N <= 32 ? 1 : 2; }
 
 static int tn_direct_splits(int64_t Kd, int M, int N) {
@@ -581,12 +768,29 @@ static int tn_direct_splits(int64_t Kd, int M, int N) {
 }
 
 size_t gemm_tn_direct_ws_bytes(int64_t Kd, int M, int N) {
-  return sizeof(float) * (size_t)tn_direct_splits(Kd, M, N) * (size_t)M * (size_t)N;
+  const int ns = std::max(tn_direct_splits(Kd, M, N), tn_wide_splits(Kd, M, N));
+  return sizeof(float) * (size_t)ns * (size_t)M * (size_t)N;
 }
 
 int gemm_tn_direct_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype,
                             float* partial, int* nsplit_out, hipStream_t s) {
   TnDirectArgs a{A, lda, B, ldb, Kd, M, N, 0, 0, partial};
+  if (tn_wide_ok(A, lda, B, ldb, N, dtype)) {
+    a.nsplit = tn_wide_splits(Kd, M, N);
+    a.rows_per_split = round_up(ceil_div(Kd > 0 ? Kd : 1, a.nsplit), 2 * kTnMaxUK);
+    *nsplit_out = a.nsplit;
+    const int tnw = N <= 32 ? 1 : 2, wnw = tn_wide_wn(N);
+    dim3 grid((unsigned)a.nsplit, (unsigned)ceil_div(M, 128), (unsigned)ceil_div(N, 32 * tnw * wnw));
+#define GCN_TN_WIDE(TT)                                                                   \
+    if (tnw == 1) k_gemm_tn_wide<TT, 1, kWideUK1, 1><<<grid, 256, 0, s>>>(a);               \
+    else if (wnw == 1) k_gemm_tn_wide<TT, 2, kWideUK2, 1><<<grid, 256, 0, s>>>(a);          \
+    else if (wnw == 2) k_gemm_tn_wide<TT, 2, kWideUK2, 2><<<grid, 256, 0, s>>>(a);          \
+    else k_gemm_tn_wide<TT, 2, kWideUK2, 4><<<grid, 256, 0, s>>>(a);
+    if (dtype == GCN_BF16) { GCN_TN_WIDE(bf16_t) } else { GCN_TN_WIDE(float) }
+#undef GCN_TN_WIDE
+    GCN_CHECK_LAUNCH();
+    return GCN_OK;
+  }
   a.nsplit = tn_direct_splits(Kd, M, N);
   a.rows_per_split = round_up(ceil_div(Kd > 0 ? Kd : 1, a.nsplit), 2 * kTnMaxUK);
   *nsplit_out = a.nsplit;
