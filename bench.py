@@ -181,6 +181,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2_rmat18")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--natural-ids", action="store_true",
+                    help="c2_rmat18 only: keep the generator's vertex numbering instead of the seeded random relabelling "
+                         "(an extra figure; the workload as specified relabels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--backward", default="push", choices=["push", "pull"],
                     help="push: dH = A^T (G W^T) with contributions to halo rows (the default, any graph); "
@@ -206,7 +209,9 @@ def main():
     bf16 = args.dtype == "bf16"
 
     t0 = time.time()
-    w = configs.get(args.workload)
+    if args.natural_ids and args.workload != "c2_rmat18":
+        raise SystemExit("--natural-ids applies to c2_rmat18")
+    w = configs.get(args.workload, permute=False) if args.natural_ids else configs.get(args.workload)
     n, dims = w["n"], w["dims"]
     log(f"workload {args.workload}: n={n} raw directed edges={w['src'].size} dims={dims} generated in {time.time() - t0:.1f}s")
 
@@ -319,7 +324,8 @@ def main():
     # HBM-side bytes per launch of that kernel, from the rocprofv3 counter runs summarised under profiles/
     # (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size): a line "bench-traffic: ..." there
     traffic_file = os.path.join(ROOT, "profiles", f"epoch_{args.workload}_{args.dtype}.md")
-    if os.path.exists(traffic_file):
+    # (measured for the workload as specified, the default plan: other variants report no traffic)
+    if os.path.exists(traffic_file) and not args.natural_ids and args.backward == "push":
         want = f"kernel={dom['kind']} d={dom['d']} "
         for line in open(traffic_file):
             if line.startswith("bench-traffic:") and want in line:
@@ -335,7 +341,7 @@ def main():
     out = {"metric": "GCN full-batch epoch ms (fwd+bwd) on 1 MI355X", "value": round(ms_per_step, 4), "unit": "ms/epoch",
            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
            "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-           "config": {"workload": args.workload, "backward": args.backward, "halo_overlap": ep.overlap, "n": n, "owned_rows": A.nr, "halo_rows": A.nh, "nnz": A.nnz, "dims": dims,
+           "config": {"workload": args.workload + ("+natural-ids" if args.natural_ids else ""), "backward": args.backward, "halo_overlap": ep.overlap, "n": n, "owned_rows": A.nr, "halo_rows": A.nh, "nnz": A.nnz, "dims": dims,
                       "layers": len(dims) - 1},
            "epochs_per_s": round(1e3 / ms_per_step, 2), "loss": round(loss, 6), "csr_csc_build_ms": round(build_ms, 2),
            "roofline": roof, "kernels": kernels, "kernels_from": f"a separate pass of {bsteps} epochs with every launch timed",
