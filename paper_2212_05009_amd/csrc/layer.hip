@@ -129,9 +129,13 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
         GCN_TRY(spmm_launch(sp, hub, s));
         if (dH) {
           GCN_TRY(transpose_f32(W, d_in, d_out, Wt, s));
+          // owned rows carry the ReLU mask, halo rows do not: two calls, so that each is uniform in its epilogue
           GemmEpilogue epi;
           epi.mask = Zprev; epi.ldmask = d_in; epi.mask_rows = Zprev ? A->nr : 0;
-          GCN_TRY(gemm_nn(T, ldt, Wt, d_in, dH, d_in, A->nc, d_in, d_out, dtype, epi, s));
+          GCN_TRY(gemm_nn(T, ldt, Wt, d_in, dH, d_in, A->nr, d_in, d_out, dtype, epi, s));
+          if (A->nh > 0)
+            GCN_TRY(gemm_nn((const char*)T + (size_t)A->nr * ldt * es, ldt, Wt, d_in, (char*)dH + (size_t)A->nr * d_in * es, d_in,
+                            A->nh, d_in, d_out, dtype, GemmEpilogue(), s));
         }
         if (AH_saved) GCN_TRY(gemm_tn(AH_saved, d_in, G, d_out, dW, d_out, A->nr, d_in, d_out, dtype, tn, s));
         else GCN_TRY(gemm_tn(H, ldh, T, ldt, dW, d_out, A->nc, d_in, d_out, dtype, tn, s));
