@@ -216,6 +216,10 @@ int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, in
 // streaming variants (gemm_direct.hip): the long operand goes from global memory straight into the
 // MFMA operand registers; nn_direct needs W to fit in LDS (gemm_nn_direct_ok)
 bool gemm_nn_direct_ok(int N, int K);
+// bf16 features on the bf16 matrix pipe (gemm_bf16.hip): W rounded to bf16 in LDS, fp32 accumulation
+bool gemm_nn_bf16_ok(const void* A, int64_t lda, void* C, int64_t ldc, int64_t M, int N, int K, const GemmEpilogue& epi);
+int gemm_nn_bf16(const void* A, int64_t lda, const float* W, int64_t ldw, void* C, int64_t ldc, int64_t M, int N, int K,
+                 const GemmEpilogue& epi, hipStream_t s);
 int gemm_nn_direct(const void* A, int64_t lda, const float* W, int64_t ldw, void* C, int64_t ldc, int64_t M, int N,
                    int K, int dtype, const GemmEpilogue& epi, hipStream_t s);
 size_t gemm_tn_direct_ws_bytes(int64_t Kd, int M, int N);
