@@ -218,6 +218,13 @@ int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, in
 bool gemm_nn_direct_ok(int N, int K);
 // bf16 features on the bf16 matrix pipe (gemm_bf16.hip): W rounded to bf16 in LDS, fp32 accumulation
 bool gemm_nn_bf16_ok(const void* A, int64_t lda, void* C, int64_t ldc, int64_t M, int N, int K, const GemmEpilogue& epi);
+// A^T B for bf16 operands on the bf16 matrix pipe: partial tiles per row split, as gemm_tn_direct_partials
+bool gemm_tn_bf16_ok(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N);
+int gemm_tn_bf16_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, float* partial,
+                          int* nsplit_out, hipStream_t s);
+// launch shape shared by the vector-request A^T B kernels: column tiles of B per block, number of row splits
+int tn_wide_wn(int N);
+int tn_wide_splits(int64_t Kd, int M, int N);
 int gemm_nn_bf16(const void* A, int64_t lda, const float* W, int64_t ldw, void* C, int64_t ldc, int64_t M, int N, int K,
                  const GemmEpilogue& epi, hipStream_t s);
 int gemm_nn_direct(const void* A, int64_t lda, const float* W, int64_t ldw, void* C, int64_t ldc, int64_t M, int N,

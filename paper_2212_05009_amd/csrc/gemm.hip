@@ -258,7 +258,7 @@ int gemm_nn(const void* A, int64_t lda, const float* B, int64_t ldb, void* C, in
             int K, int dtype, const GemmEpilogue& epi, hipStream_t s) {
   if (M == 0) return GCN_OK;
   const size_t es = dtype == GCN_BF16 ? 2 : 4;
-  if (dtype == GCN_BF16 && use_direct() && ldb == N && gemm_nn_bf16_ok(A, lda, C, ldc, M, N, K, epi)) {
+  if (dtype == GCN_BF16 && use_direct() && gemm_nn_bf16_ok(A, lda, C, ldc, M, N, K, epi)) {
     const double nb = 2.0 * (double)M * (K + N * (epi.C2 ? 2.0 : 1.0) + (epi.mask ? N : 0)) + 4.0 * (double)K * N;
     ProfScope ps(GCN_K_GEMM_NN, s, N, dtype, M, K, nb, nb, 2.0 * (double)M * N * K);
     return gemm_nn_bf16(A, lda, B, ldb, C, ldc, M, N, K, epi, s);

@@ -745,10 +745,10 @@ static bool tn_wide_ok(const void* A, int64_t lda, const void* B, int64_t ldb, i
 }
 
 // column tiles of B per block in the vector variant: all of B for up to 256 columns
-static int tn_wide_wn(int N) { return N <= 64 ? 1 : N <= 128 ? 2 : 4; }
+int tn_wide_wn(int N) { return N <= 64 ? 1 : N <= 128 ? 2 : 4; }
 
 // splits of the vector variant: about two blocks per compute unit
-static int tn_wide_splits(int64_t Kd, int M, int N) {
+int tn_wide_splits(int64_t Kd, int M, int N) {
   static const int blocks = [] { const char* e = getenv("GCN_GEMM_TN_BLOCKS"); const int v = e ? atoi(e) : 0; return v > 0 ? v : 512; }();
   const int64_t tiles = ceil_div(M, 128) * ceil_div(N, (N <= 32 ? 32 : 64) * tn_wide_wn(N));
   int64_t want = ceil_div(blocks, tiles);
@@ -774,6 +774,8 @@ size_t gemm_tn_direct_ws_bytes(int64_t Kd, int M, int N) {
 
 int gemm_tn_direct_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype,
                             float* partial, int* nsplit_out, hipStream_t s) {
+  if (dtype == GCN_BF16 && gemm_tn_bf16_ok(A, lda, B, ldb, Kd, M, N))
+    return gemm_tn_bf16_partials(A, lda, B, ldb, Kd, M, N, partial, nsplit_out, s);
   TnDirectArgs a{A, lda, B, ldb, Kd, M, N, 0, 0, partial};
   if (tn_wide_ok(A, lda, B, ldb, N, dtype)) {
     a.nsplit = tn_wide_splits(Kd, M, N);
