@@ -16,16 +16,22 @@ static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 static size_t es_of(int dtype) { return dtype == GCN_BF16 ? 2 : 4; }
 
 // Leading dimension of an internal buffer whose rows a sparse product gathers.  A row that starts at a multiple
-// of s bytes and is s bytes long touches (s + 128 - gcd(s, 128)) / 128 lines of 128 bytes on average: rounding
-// the row up to 64 bytes instead of 16 is taken when it saves lines (width 41: 176 -> 192 bytes, 2.25 -> 2 lines).
+// of s bytes and is s bytes long touches (s + 128 - gcd(s, 128)) / 128 lines of 128 bytes on average.  The row is
+// rounded up to 16 bytes, or to 64 or 128 bytes where that saves at least 8 % of the lines for at most half as
+// many bytes again (fp32 width 41: 176 -> 192 bytes, 2.25 -> 2 lines; bf16 width 47: 96 -> 128 bytes, 1.5 -> 1).
 static int64_t gather_ld(int d, size_t es) {
-  auto lines = [&](int64_t ld) {
-    int64_t sb = ld * (int64_t)es, g = 128;
+  auto lines = [](int64_t sb) {
+    int64_t g = 128;
     while (sb % g) g >>= 1;
     return (double)(sb + 128 - g) / 128.0;
   };
-  const int64_t a = round_up(d, 4), b = round_up(d, 16);
-  return lines(b) <= 0.92 * lines(a) ? b : a;
+  const int64_t base = round_up((int64_t)d * (int64_t)es, 16);
+  int64_t best = base;
+  for (int64_t unit : {64, 128}) {
+    const int64_t cand = round_up((int64_t)d * (int64_t)es, unit);
+    if (cand * 2 <= base * 3 && lines(cand) <= 0.92 * lines(best)) best = cand;
+  }
+  return best / (int64_t)es;
 }
 
 struct Carver {              // hands out 256-byte aligned pieces of the workspace
