@@ -208,8 +208,8 @@ __global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <
 }
 
 // ---- the same product without a single data-dependent branch ----------------------------------------
-// For operands whose rows are 16-byte aligned, K = 16 KU with KU = 1, 2, 4 (the whole row in one request)
-// or a multiple of 128 (KU = 8), N a multiple of 16 and a mask that covers every row.  Every load is an
+// For operands whose rows are 16-byte aligned (fp32; 8-byte for bf16), K up to 128 (KU = ceil(K / 16) k steps, the
+// whole row in one request batch, a tail of the row cleared by bit masks) or a multiple of 128 (KU = 8), N up to 256 and a mask that covers every row.  Every load is an
 // unconditional 16-byte (bf16: 8-byte) request - rows beyond M are clamped to the last row and dropped at
 // the store - so the compiler can keep the next step's operand loads in flight across the MFMAs of the
 // current one instead of waiting at every join of the general kernel's bounds checks.
@@ -244,11 +244,12 @@ __global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <
   constexpr int LDW = NT * 16 + 4;
   constexpr bool kQuad = NT % 4 == 0;
   constexpr int TQ = kQuad ? NT / 4 : 1;
-  for (int e = threadIdx.x; e < a.K * NT * 16; e += kNnThreads) {
+  const int chunks = (a.K + 16 * KU - 1) / (16 * KU);   // k chunks per tile
+  for (int e = threadIdx.x; e < chunks * 16 * KU * NT * 16; e += kNnThreads) {      // zero beyond K and N
     const int k = e / (NT * 16), n = e % (NT * 16);
     const int t = n >> 4, cc = n & 15;
     const int at = kQuad ? ((k * TQ + (t >> 2)) * 16 + cc) * 4 + (t & 3) : k * LDW + n;
-    Ws[at] = a.W[(int64_t)k * a.ldw + n];
+    Ws[at] = (k < a.K && n < a.N) ? a.W[(int64_t)k * a.ldw + n] : 0.f;
   }
   __syncthreads();
 
@@ -261,21 +262,31 @@ __global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <
   constexpr int WPB = kNnThreads / 64;
   const int64_t ntiles = (a.M + 15) / 16;
   const int64_t stride = (int64_t)gridDim.x * WPB;
-  const int chunks = a.K / (16 * KU);                 // k chunks per tile
   // mask values of the next tile travel with its operand rows when a tile is a single chunk and they fit
   constexpr bool kPrefetchMask = MASK && KU <= 2 && NT <= 8;
 
+  // K that is no multiple of 16: the lane's request of the very last k step may start past K (moved to column 0)
+  // or reach past it (the row is padded to 4 elements); `tail` clears what is not part of the product
+  const int k_last = 16 * KU * chunks - 16 + 4 * q;
+  const int n_ok = a.K - k_last;
+  const int last_off = n_ok > 0 ? k_last : 0;
+  uint32_t tail[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) tail[i] = i < n_ok ? 0xffffffffu : 0u;
+  const int n_up = (a.N + 3) & ~3;                      // columns come in groups of 4; the rows are that long
   auto load_a = [&](int64_t tile, int chunk, float (&av)[KU][4]) {
     const int64_t row = tile * 16 + c;
-    const T* __restrict__ arow = A + (row < a.M ? row : a.M - 1) * a.lda + chunk * (16 * KU) + 4 * q;
+    const T* __restrict__ arow = A + (row < a.M ? row : a.M - 1) * a.lda;
+    const bool last = chunk == chunks - 1;
 #pragma unroll
-    for (int u = 0; u < KU; ++u) vload4<T>(arow + 16 * u, av[u]);
+    for (int u = 0; u < KU; ++u)
+      vload4<T>(arow + ((u == KU - 1 && last) ? last_off : chunk * (16 * KU) + 16 * u + 4 * q), av[u]);
   };
   auto load_m = [&](int64_t tile, float (&keep)[NT][4]) {
     const int64_t row = tile * 16 + c;
-    const T* __restrict__ mrow = Mk + (row < a.M ? row : a.M - 1) * a.ldmask + 4 * q;
+    const T* __restrict__ mrow = Mk + (row < a.M ? row : a.M - 1) * a.ldmask;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) vload4<T>(mrow + 16 * t, keep[t]);
+    for (int t = 0; t < NT; ++t) vload4<T>(mrow + (16 * t + 4 * q < n_up ? 16 * t + 4 * q : 0), keep[t]);
   };
 
   int64_t tile = (int64_t)blockIdx.x * WPB + w;
@@ -301,6 +312,10 @@ __global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <
       for (int u = 0; u < KU; ++u)
 #pragma unroll
         for (int i = 0; i < 4; ++i) av[u][i] = a_nxt[u][i];
+      if (chunk == chunks - 1) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) av[KU - 1][i] = __uint_as_float(__float_as_uint(av[KU - 1][i]) & tail[i]);
+      }
       // the next request: this tile's next chunk, else the first chunk of the wavefront's next tile
       // (clamped to the last tile: a valid, wasted load at the very end)
       const bool same = chunk + 1 < chunks;
@@ -348,11 +363,12 @@ __global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int n = t * 16 + 4 * q;
+        if (n >= n_up) continue;
         float v[4], pre[4], kp[4];
         if constexpr (MASK && !kPrefetchMask) vload4<T>(Mk + m * a.ldmask + n, kp);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          pre[r] = acc[t][r] + (a.bias ? a.bias[n + r] : 0.f);
+          pre[r] = acc[t][r] + ((a.bias && n + r < a.N) ? a.bias[n + r] : 0.f);
           v[r] = a.relu ? (pre[r] > 0.f ? pre[r] : 0.f) : pre[r];
           if constexpr (MASK) v[r] = (kPrefetchMask ? keep[t][r] : kp[r]) > 0.f ? v[r] : 0.f;
         }
@@ -402,19 +418,27 @@ static int nn_launch_fast(const NnDirectArgs& a, hipStream_t s) {
   return a.C2 ? go(k_gemm_nn_fast<T, NT, KU, false, true>) : go(k_gemm_nn_fast<T, NT, KU, false, false>);
 }
 
-// the branch-free kernel serves the layer shapes (N = 16 NT, K = 16, 32, 64 or a multiple of 128, aligned rows)
+// the branch-free kernel serves aligned rows with K up to 128 or a multiple of 128
 template <typename T>
 static bool nn_fast(const NnDirectArgs& a, hipStream_t s, int* rc) {
   static const bool off = getenv("GCN_GEMM_FAST") && atoi(getenv("GCN_GEMM_FAST")) == 0;
   const int NT = nn_tiles(a.N);
-  if (off || a.N != NT * 16 || a.vecA != 4 || a.vecC != 4 || (a.C2 && a.vecC2 != 4)) return false;
+  if (off || a.vecA != 4 || a.vecC != 4 || (a.C2 && a.vecC2 != 4)) return false;
   if (a.mask && (a.vecM != 4 || a.mask_rows < a.M || a.C2)) return false;
-  const int ku = a.K % 128 == 0 ? 8 : a.K == 64 ? 4 : a.K == 32 ? 2 : a.K == 16 ? 1 : 0;
+  const int ku = a.K % 128 == 0 ? 8 : a.K < 128 ? (a.K + 15) / 16 : 0;
   if (ku == 0) return false;
 #define GCN_NN_FAST(NTV)                                              \
   {                                                                   \
-    *rc = ku == 1 ? nn_launch_fast<T, NTV, 1>(a, s) : ku == 2 ? nn_launch_fast<T, NTV, 2>(a, s) \
-        : ku == 4 ? nn_launch_fast<T, NTV, 4>(a, s) : nn_launch_fast<T, NTV, 8>(a, s);          \
+    switch (ku) {                                                     \
+      case 1: *rc = nn_launch_fast<T, NTV, 1>(a, s); break;           \
+      case 2: *rc = nn_launch_fast<T, NTV, 2>(a, s); break;           \
+      case 3: *rc = nn_launch_fast<T, NTV, 3>(a, s); break;           \
+      case 4: *rc = nn_launch_fast<T, NTV, 4>(a, s); break;           \
+      case 5: *rc = nn_launch_fast<T, NTV, 5>(a, s); break;           \
+      case 6: *rc = nn_launch_fast<T, NTV, 6>(a, s); break;           \
+      case 7: *rc = nn_launch_fast<T, NTV, 7>(a, s); break;           \
+      default: *rc = nn_launch_fast<T, NTV, 8>(a, s); break;          \
+    }                                                                 \
     return true;                                                      \
   }
   switch (NT) {
