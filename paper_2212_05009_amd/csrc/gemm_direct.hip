@@ -236,7 +236,8 @@ template <typename T> __device__ __forceinline__ void vstore4(T* __restrict__ p,
   }
 }
 
-template <typename T, int NT, int KU, bool MASK, bool SAVE>
+// FULL: K is a multiple of 16 and N = 16 NT, so there is no tail to clear and no column group to skip
+template <typename T, int NT, int KU, bool MASK, bool SAVE, bool FULL>
 __global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <= 8 ? 4 : 2, 8))) void k_gemm_nn_fast(NnDirectArgs a) {
   // W in LDS.  NT a multiple of 4: [k][t / 4][c][t % 4], so that the four column tiles 4 tq .. 4 tq + 3 of a
   // lane's (k, c) are one 16-byte read and the 16 lanes of a k row read 256 contiguous bytes.  Else [k][LDW].
@@ -273,20 +274,26 @@ __global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <
   uint32_t tail[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) tail[i] = i < n_ok ? 0xffffffffu : 0u;
-  const int n_up = (a.N + 3) & ~3;                      // columns come in groups of 4; the rows are that long
+  const int n_up = FULL ? NT * 16 : (a.N + 3) & ~3;     // columns come in groups of 4; the rows are that long
   auto load_a = [&](int64_t tile, int chunk, float (&av)[KU][4]) {
     const int64_t row = tile * 16 + c;
-    const T* __restrict__ arow = A + (row < a.M ? row : a.M - 1) * a.lda;
-    const bool last = chunk == chunks - 1;
+    if constexpr (FULL) {
+      const T* __restrict__ arow = A + (row < a.M ? row : a.M - 1) * a.lda + chunk * (16 * KU) + 4 * q;
 #pragma unroll
-    for (int u = 0; u < KU; ++u)
-      vload4<T>(arow + ((u == KU - 1 && last) ? last_off : chunk * (16 * KU) + 16 * u + 4 * q), av[u]);
+      for (int u = 0; u < KU; ++u) vload4<T>(arow + 16 * u, av[u]);
+    } else {
+      const T* __restrict__ arow = A + (row < a.M ? row : a.M - 1) * a.lda;
+      const bool last = chunk == chunks - 1;
+#pragma unroll
+      for (int u = 0; u < KU; ++u)
+        vload4<T>(arow + ((u == KU - 1 && last) ? last_off : chunk * (16 * KU) + 16 * u + 4 * q), av[u]);
+    }
   };
   auto load_m = [&](int64_t tile, float (&keep)[NT][4]) {
     const int64_t row = tile * 16 + c;
     const T* __restrict__ mrow = Mk + (row < a.M ? row : a.M - 1) * a.ldmask;
 #pragma unroll
-    for (int t = 0; t < NT; ++t) vload4<T>(mrow + (16 * t + 4 * q < n_up ? 16 * t + 4 * q : 0), keep[t]);
+    for (int t = 0; t < NT; ++t) vload4<T>(mrow + ((FULL || 16 * t + 4 * q < n_up) ? 16 * t + 4 * q : 0), keep[t]);
   };
 
   int64_t tile = (int64_t)blockIdx.x * WPB + w;
@@ -312,9 +319,11 @@ __global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <
       for (int u = 0; u < KU; ++u)
 #pragma unroll
         for (int i = 0; i < 4; ++i) av[u][i] = a_nxt[u][i];
-      if (chunk == chunks - 1) {
+      if constexpr (!FULL) {
+        if (chunk == chunks - 1) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) av[KU - 1][i] = __uint_as_float(__float_as_uint(av[KU - 1][i]) & tail[i]);
+          for (int i = 0; i < 4; ++i) av[KU - 1][i] = __uint_as_float(__float_as_uint(av[KU - 1][i]) & tail[i]);
+        }
       }
       // the next request: this tile's next chunk, else the first chunk of the wavefront's next tile
       // (clamped to the last tile: a valid, wasted load at the very end)
@@ -363,12 +372,12 @@ __global__ __launch_bounds__(kNnThreads) __attribute__((amdgpu_waves_per_eu(NT <
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int n = t * 16 + 4 * q;
-        if (n >= n_up) continue;
+        if constexpr (!FULL) { if (n >= n_up) continue; }
         float v[4], pre[4], kp[4];
         if constexpr (MASK && !kPrefetchMask) vload4<T>(Mk + m * a.ldmask + n, kp);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          pre[r] = acc[t][r] + ((a.bias && n + r < a.N) ? a.bias[n + r] : 0.f);
+          pre[r] = acc[t][r] + ((a.bias && (FULL || n + r < a.N)) ? a.bias[n + r] : 0.f);
           v[r] = a.relu ? (pre[r] > 0.f ? pre[r] : 0.f) : pre[r];
           if constexpr (MASK) v[r] = (kPrefetchMask ? keep[t][r] : kp[r]) > 0.f ? v[r] : 0.f;
         }
@@ -414,8 +423,14 @@ static int nn_launch_fast(const NnDirectArgs& a, hipStream_t s) {
     GCN_CHECK_LAUNCH();
     return GCN_OK;
   };
-  if (a.mask) return go(k_gemm_nn_fast<T, NT, KU, true, false>);
-  return a.C2 ? go(k_gemm_nn_fast<T, NT, KU, false, true>) : go(k_gemm_nn_fast<T, NT, KU, false, false>);
+  if constexpr (KU == 1 || KU == 2 || KU == 4 || KU == 8) {
+    if ((a.K % 16) == 0 && a.N == NT * 16) {
+      if (a.mask) return go(k_gemm_nn_fast<T, NT, KU, true, false, true>);
+      return a.C2 ? go(k_gemm_nn_fast<T, NT, KU, false, true, true>) : go(k_gemm_nn_fast<T, NT, KU, false, false, true>);
+    }
+  }
+  if (a.mask) return go(k_gemm_nn_fast<T, NT, KU, true, false, false>);
+  return a.C2 ? go(k_gemm_nn_fast<T, NT, KU, false, true, false>) : go(k_gemm_nn_fast<T, NT, KU, false, false, false>);
 }
 
 // the branch-free kernel serves aligned rows with K up to 128 or a multiple of 128
