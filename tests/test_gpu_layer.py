@@ -280,10 +280,13 @@ def test_two_layer_epoch_config1(gcn, dev, er, c1, bf16):
 
 # row counts around the kernels' tile and chunk sizes (16-row tiles, 16-row request batches, 512-row splits),
 # widths that pick each dense kernel variant (vector requests: d_in a multiple of 4; side-by-side tiles of
-# the second operand for d_out up to 64, 128, 256; branch-free product for K = 16, 32, 64, 128)
+# the second operand for d_out up to 64, 128, 256; branch-free product with and without a tail in K and N;
+# bf16 features on the bf16 matrix pipe)
 @pytest.mark.parametrize("rows", [1, 2, 3, 15, 17, 33, 511, 513, 1025, 8191, 70001])
 @pytest.mark.parametrize("d_in,d_out,bf16", [(128, 128, False), (128, 16, False), (16, 128, True), (100, 256, False),
-                                               (64, 40, False), (32, 200, True), (36, 129, False), (7, 5, False)])
+                                               (64, 40, False), (32, 200, True), (36, 129, False), (7, 5, False),
+                                               (128, 128, True), (100, 256, True), (256, 47, True), (47, 256, True),
+                                               (256, 256, True), (44, 41, True), (47, 256, False), (256, 47, False)])
 def test_dense_kernels_over_row_counts(gcn, dev, rows, d_in, d_out, bf16):
     case = Case(gcn, dev, np.zeros(0, np.int32), np.zeros(0, np.int32), rows)          # A^ = I
     run_fwd(gcn, dev, case, d_in, d_out, bf16=bf16, bias=True, save_ah=True)
