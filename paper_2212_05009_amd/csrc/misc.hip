@@ -208,6 +208,71 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, i
   if (threadIdx.x == 0) g_loss_partial[blockIdx.x] = red[0];
 }
 
+// The same for rows of 4 LPR >= C classes with 16-byte (fp32) / 8-byte (bf16) aligned rows and C a multiple of 4:
+// a lane holds 4 classes, so a row is one vector load and one vector store per lane and two or three shuffle steps.
+template <typename T, int LPR>
+__global__ __launch_bounds__(256) void k_softmax_xent_v4(const T* __restrict__ Z, int64_t ldz, int64_t nr, int C,
+                                                         const int32_t* __restrict__ y, float scale,
+                                                         T* __restrict__ G, int64_t ldg) {
+  constexpr int GR = 256 / LPR;
+  const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
+  const bool in = 4 * l < C;
+  double local = 0.0;
+  for (int64_t row = (int64_t)blockIdx.x * GR + g; row < nr; row += (int64_t)gridDim.x * GR) {
+    const int label = y[row];
+    float z[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    if (in) {
+      if constexpr (sizeof(T) == 4) {
+        const float4 v = *reinterpret_cast<const float4*>(Z + row * ldz + 4 * l);
+        z[0] = v.x; z[1] = v.y; z[2] = v.z; z[3] = v.w;
+      } else {
+        const uint2 v = *reinterpret_cast<const uint2*>(Z + row * ldz + 4 * l);
+        z[0] = __uint_as_float(v.x << 16); z[1] = __uint_as_float(v.x & 0xffff0000u);
+        z[2] = __uint_as_float(v.y << 16); z[3] = __uint_as_float(v.y & 0xffff0000u);
+      }
+    }
+    const bool labelled = label >= 0 && label < C;
+    float mx = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    float e[4], se = 0.f, zl = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      e[i] = in ? expf(z[i] - mx) : 0.f;
+      se += e[i];
+      if (4 * l + i == label) zl = z[i];               // the label's logit, in one lane of the row
+    }
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) { se += __shfl_xor(se, off, 64); zl += __shfl_xor(zl, off, 64); }
+    if (in) {
+      const float inv = 1.0f / se;
+      float o[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[i] = labelled ? scale * (e[i] * inv - (4 * l + i == label ? 1.f : 0.f)) : 0.f;
+      if constexpr (sizeof(T) == 4) {
+        *reinterpret_cast<float4*>(G + row * ldg + 4 * l) = make_float4(o[0], o[1], o[2], o[3]);
+      } else {
+        T h[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) stf<T>(&h[i], o[i]);
+        uint2 pk;
+        pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+        pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+        *reinterpret_cast<uint2*>(G + row * ldg + 4 * l) = pk;
+      }
+    }
+    if (l == 0 && labelled) local += (double)(mx + logf(se)) - (double)zl;
+  }
+  __shared__ double red[256];
+  red[threadIdx.x] = local;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) g_loss_partial[blockIdx.x] = red[0];
+}
+
 // one block: thread t adds the partials t, t+256, ... in order, then a fixed tree over the threads
 __global__ __launch_bounds__(256) void k_loss_finish(int nblocks, float scale, float* __restrict__ loss) {
   __shared__ double red[256];
@@ -230,6 +295,27 @@ __global__ __launch_bounds__(256) void k_loss_finish(int nblocks, float scale, f
 template <typename T>
 static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* y, float scale, float* loss, T* G,
                      int64_t ldg, hipStream_t s) {
+  const size_t vb = 4 * sizeof(T);
+  if (C % 4 == 0 && C <= 256 && (ldz % 4) == 0 && (ldg % 4) == 0 && ((uintptr_t)Z % vb) == 0 && ((uintptr_t)G % vb) == 0) {
+    int lpr4 = 1;
+    while (4 * lpr4 < C) lpr4 <<= 1;
+    int64_t want4 = ceil_div(nr > 0 ? nr : 1, 256 / lpr4);
+    const int nb4 = (int)(want4 < kLossBlocks ? want4 : kLossBlocks);
+    const double by4 = (double)nr * (2.0 * sizeof(T) * C + 4.0);
+    ProfScope ps(GCN_K_SOFTMAX_XENT, s, C, sizeof(T) == 2 ? GCN_BF16 : GCN_F32, nr, 0, by4, by4, 0.0);
+    switch (lpr4) {
+      case 1: k_softmax_xent_v4<T, 1><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      case 2: k_softmax_xent_v4<T, 2><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      case 4: k_softmax_xent_v4<T, 4><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      case 8: k_softmax_xent_v4<T, 8><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      case 16: k_softmax_xent_v4<T, 16><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      case 32: k_softmax_xent_v4<T, 32><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      default: k_softmax_xent_v4<T, 64><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+    }
+    k_loss_finish<<<1, 256, 0, s>>>(nb4, scale, loss);
+    GCN_CHECK_LAUNCH();
+    return GCN_OK;
+  }
   int lpr = 4;
   while (lpr < 64 && lpr < C) lpr <<= 1;
   int64_t want = ceil_div(nr > 0 ? nr : 1, 256 / lpr);

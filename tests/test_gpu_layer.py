@@ -185,7 +185,7 @@ def test_layer_bwd_hubs_and_directed_block(gcn, dev, hubs, directed_block):
 
 
 # ----------------------------------------------------------------------------- softmax cross-entropy
-@pytest.mark.parametrize("C", [1, 2, 8, 16, 32, 41, 47, 100])
+@pytest.mark.parametrize("C", [1, 2, 4, 8, 12, 16, 32, 41, 47, 64, 100, 256])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_softmax_xent(gcn, dev, C, bf16):
     import torch
