@@ -779,6 +779,7 @@ static bool tn_wide_ok(const void* A, int64_t lda, const void* B, int64_t ldb, i
   static const bool off = getenv("GCN_GEMM_TN_WIDE") && atoi(getenv("GCN_GEMM_TN_WIDE")) == 0;
   const size_t es = dtype == GCN_BF16 ? 2 : 4;
   if (off || (lda % 4) != 0 || ((uintptr_t)A % (4 * es)) != 0) return false;
+  if (lda >= (1 << 28) || ldb >= (1 << 28)) return false;      // a lane's offset (one row + a column, in bytes) is kept in 32 bits
   if (N > 32 && ((ldb % 2) != 0 || ((uintptr_t)B % (2 * es)) != 0)) return false;
   return true;
 }
