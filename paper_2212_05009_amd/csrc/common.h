@@ -193,6 +193,8 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s);
 // column-sweep variant (spmm_panel.hip): *used = false when the product does not qualify and
 // nothing was enqueued
 int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used);
+// whether spmm_panel_try would take this product (a.X only matters for its alignment)
+bool spmm_panel_wanted(const SpmmArgs& a);
 void free_panel_plans(gcn_csr* A);
 // ptr[q] = first position whose key >> shift is >= q, q in [0, n_seg]; keys sorted, n >= 1
 int segment_boundaries(const uint64_t* keys, int64_t n, int shift, int64_t n_seg, int64_t* ptr, hipStream_t s);

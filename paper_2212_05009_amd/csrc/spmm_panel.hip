@@ -717,31 +717,30 @@ void free_panel_plans(gcn_csr* A) {
   A->plans.clear();
 }
 
-int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used) {
-  *used = false;
+// Whether the column sweep serves this product, and in which shape: lane-group width sw (features), lanes per
+// group, feature slices ns, and the column-block size 2^cb_shift.
+static bool panel_shape(const SpmmArgs& a, int* sw_out, int* lpg_out, int* ns_out, int* cb_shift_out) {
   const char* env = getenv("GCN_SPMM_PANEL");            // 0: never, 1: whenever the limits allow
   const int force = env ? atoi(env) : -1;
-  if (force == 0 || !a.owner || a.n_rows < 1 || a.nnz < 1) return GCN_OK;
+  if (force == 0 || !a.owner || a.n_rows < 1 || a.nnz < 1 || a.part != 0) return false;
   const size_t es = a.dtype == GCN_BF16 ? 2 : 4;
   // limits of the packed entry format and of 32-bit addressing of X
   const double xspan = (double)a.n_cols * (double)a.ldx * (double)es;
   if (a.n_cols >= (1 << kColBits) - 1 || a.ldx * (int64_t)es >= (1 << 24) || xspan >= 4294967296.0 || a.nnz >= 0xffffffffLL)
-    return GCN_OK;
+    return false;
   // the gathers are 16-byte vector loads
   auto aligned = [](const void* p, size_t al) { return ((uintptr_t)p % al) == 0; };
   const int V = a.dtype == GCN_BF16 ? 8 : 4;
-  if (!((a.ldx % V) == 0 && aligned(a.X, 16) && ((a.d % V) == 0 || a.x_rows_padded))) return GCN_OK;
+  if (!((a.ldx % V) == 0 && aligned(a.X, 16) && ((a.d % V) == 0 || a.x_rows_padded))) return false;
   // lane-group shape: half a wavefront per row (128 fp32 features) for wide fp32 products, else 32
   // features per group (16 for products no wider than that)
   const bool wide = a.dtype == GCN_F32 && a.d >= 64 && !getenv("GCN_PANEL_NARROW");
   const int sw = wide ? 128 : a.d <= 16 ? 16 : 32;
-  const int lpg = sw / V;
   const int ns = (int)ceil_div(a.d, sw);
   // bytes of L2 one row of the operand occupies in an XCD that works on one slice
   const double foot = ns == 1 ? (double)a.d * (double)es : std::max(128.0, (double)sw * (double)es);
   int cb_shift = 10;
   while (cb_shift < 20 && (double)(2LL << cb_shift) * foot <= 2.0 * 1024 * 1024) ++cb_shift;
-  const int n_wg = device_cus();
   if (force != 1) {
     // Worth it when (1) the operand is large enough to spill L2 and the gathers of one round re-read it
     // several times, and (2) a virtual row has several entries per column block, so that most entries
@@ -752,13 +751,28 @@ int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used) {
     // instances do not beat the row-per-wavefront kernel (they are bound by instruction issue, not bytes).
     const int cap = std::min(kMaxVrows, kLdsBudget / (sw * 4));
     const double avg = (double)a.nnz / (double)a.n_rows;
-    const double reuse = (double)(n_wg / kPanelLists) * cap * avg / (double)a.n_cols;
+    const double reuse = (double)(device_cus() / kPanelLists) * cap * avg / (double)a.n_cols;
     const double n_cb = std::ceil((double)a.n_cols / (double)(1LL << cb_shift));
     const double run = std::min(avg, 512.0) / n_cb;
     if (a.dtype != GCN_F32 || a.nnz < (1 << 20) || (double)a.n_cols * foot < 6.0 * 1024 * 1024 || reuse < 3.0 ||
         run < (wide ? 3.0 : 8.0))
-      return GCN_OK;
+      return false;
   }
+  *sw_out = sw; *lpg_out = sw / V; *ns_out = ns; *cb_shift_out = cb_shift;
+  return true;
+}
+
+bool spmm_panel_wanted(const SpmmArgs& a) {
+  int sw, lpg, ns, cb_shift;
+  return panel_shape(a, &sw, &lpg, &ns, &cb_shift);
+}
+
+int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used) {
+  *used = false;
+  int sw, lpg, ns, cb_shift;
+  if (!panel_shape(a, &sw, &lpg, &ns, &cb_shift)) return GCN_OK;
+  const size_t es = a.dtype == GCN_BF16 ? 2 : 4;
+  const int n_wg = device_cus();
 
   PanelPlan* P = nullptr;
   for (PanelPlan* p : a.owner->plans)
