@@ -320,6 +320,15 @@ int gcn_profile_filter(int kind_mask, int d);
 int64_t gcn_profile_count(int64_t* dropped);
 int gcn_profile_get(int64_t i, gcn_profile_rec* out);
 
+/* ---- launch geometry (a test hook) -------------------------------------------------------------
+ * Kernels whose grid grows with the problem size are launched with at most 2^22 blocks in the grid's x
+ * dimension and the rest in y, because a launch whose x extent reaches 2^32 threads is not refused by the
+ * runtime but run with the count taken modulo 2^32.  This call lowers that bound (1 .. 2^22; 0 restores the
+ * default) for the whole process, so that tests reach the two-dimensional form on small inputs.  Results do
+ * not depend on it.  With a bound b, a call whose kernel would need more than 65535 b blocks returns
+ * GCN_EINVAL.  Not thread-safe against launches in flight on other host threads. */
+int gcn_debug_max_grid_x(int64_t blocks);
+
 #ifdef __cplusplus
 }
 #endif

@@ -73,6 +73,8 @@ def _load():
     lib.gcn_profile_count.restype = C.c_int64
     lib.gcn_profile_get.argtypes = [C.c_int64, C.POINTER(ProfileRec)]
     lib.gcn_profile_get.restype = C.c_int
+    lib.gcn_debug_max_grid_x.argtypes = [C.c_int64]
+    lib.gcn_debug_max_grid_x.restype = C.c_int
     for name in ("gcn_csr_build", "gcn_csr_info", "gcn_csr_arrays", "gcn_csr_free", "gcn_spmm", "gcn_spmm_t",
                  "gcn_halo_gather", "gcn_layer_fwd", "gcn_layer_bwd", "gcn_softmax_xent"):
         getattr(lib, name).restype = C.c_int
@@ -380,6 +382,11 @@ def gcn_sgd_update(W: torch.Tensor, dW: torch.Tensor, lr: float):
         raise TypeError("gcn_sgd_update: W and dW must be contiguous and of one shape")
     _check(_lib.gcn_sgd_update(_ptr(W), _ptr(dW), W.numel(), float(lr), _stream()), "gcn_sgd_update")
     return W
+
+
+def gcn_debug_max_grid_x(blocks: int):
+    """Test hook: most blocks in the x dimension of a launch (0 restores the default of 2^22)."""
+    _check(_lib.gcn_debug_max_grid_x(int(blocks)), "gcn_debug_max_grid_x")
 
 
 def gcn_profile_enable(on: bool):

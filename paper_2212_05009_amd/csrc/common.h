@@ -63,6 +63,25 @@ struct DevBuf {
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 
+// Launch geometry.  The runtime does not refuse a launch whose x extent (blocks x threads per block) reaches 2^32
+// threads: it runs that count modulo 2^32 and reports success (measured on gfx950: 2^24 + 1 blocks of 256 threads ran
+// one block), while a grid of two dimensions runs completely (65536 x 65535 blocks measured).  Grids that grow with
+// the problem are therefore folded: at most max_grid_x() blocks in x, the rest in y; the kernel takes its number from
+// block_id() and checks it against the count it was given.  gcn_debug_max_grid_x() lowers the bound so that tests
+// exercise the folding on small inputs.
+int64_t max_grid_x();
+static inline dim3 fold_grid(int64_t blocks) {
+  const int64_t mx = max_grid_x();
+  if (blocks < 1) blocks = 1;
+  if (blocks <= mx) return dim3((unsigned)blocks);
+  return dim3((unsigned)mx, (unsigned)ceil_div(blocks, mx));
+}
+// blocks the runtime can take in one folded launch (y is kept within 16 bits)
+static inline bool grid_fits(int64_t blocks) { return blocks <= max_grid_x() * 65535; }
+#ifdef __HIPCC__
+__device__ __forceinline__ int64_t block_id() { return (int64_t)blockIdx.y * gridDim.x + blockIdx.x; }
+#endif
+
 // ---- execution schedule of a compressed sparse matrix (row binning) ----------------------
 // Rows are split by length.  Rows longer than kHubRowNnz ("hub" rows of a power-law graph)
 // are cut into chunks of kHubChunkNnz entries, one 256-thread block per chunk; their partial

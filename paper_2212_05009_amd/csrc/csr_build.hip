@@ -8,19 +8,19 @@
 namespace gcn {
 
 constexpr int kThreads = 256;
-static inline unsigned grid_for(int64_t n) { return (unsigned)ceil_div(n > 0 ? n : 1, kThreads); }
+static inline dim3 grid_for(int64_t n) { return fold_grid(ceil_div(n > 0 ? n : 1, kThreads)); }
 
 // ---- step 1: id validation ------------------------------------------------------------------
 __global__ void k_validate(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
                            int64_t n_edges, int64_t n_global, int* __restrict__ bad) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t e = block_id() * blockDim.x + threadIdx.x;
   if (e >= n_edges) return;
   int32_t s = src[e], t = dst[e];
   if (s < 0 || s >= n_global || t < 0 || t >= n_global) atomicOr(bad, 1);
 }
 
 __global__ void k_validate_deg(const int32_t* __restrict__ deg, int64_t n, int* __restrict__ bad) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i < n && deg[i] < 1) atomicOr(bad, 2);
 }
 
@@ -28,7 +28,7 @@ __global__ void k_validate_deg(const int32_t* __restrict__ deg, int64_t n, int* 
 __global__ void k_mark_halo(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
                             int64_t n_edges, int64_t row_lo, int64_t row_hi,
                             uint32_t* __restrict__ bitmap) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t e = block_id() * blockDim.x + threadIdx.x;
   if (e >= n_edges) return;
   int64_t s = src[e], t = dst[e];
   if (s >= row_lo && s < row_hi && (t < row_lo || t >= row_hi))
@@ -36,13 +36,13 @@ __global__ void k_mark_halo(const int32_t* __restrict__ src, const int32_t* __re
 }
 
 __global__ void k_popc(const uint32_t* __restrict__ bitmap, int64_t words, uint32_t* __restrict__ cnt) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i < words) cnt[i] = (uint32_t)__popc(bitmap[i]);
 }
 
 __global__ void k_halo_list(const uint32_t* __restrict__ bitmap, const int64_t* __restrict__ wprefix,
                             int64_t words, int32_t* __restrict__ halo_gid) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i >= words) return;
   uint32_t w = bitmap[i];
   int64_t p = wprefix[i];
@@ -60,7 +60,7 @@ __global__ void k_make_keys(const int32_t* __restrict__ src, const int32_t* __re
                             int64_t n_edges, int64_t row_lo, int64_t row_hi, int64_t nr, int colbits,
                             const uint32_t* __restrict__ bitmap, const int64_t* __restrict__ wprefix,
                             uint64_t* __restrict__ keys) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t e = block_id() * blockDim.x + threadIdx.x;
   if (e >= n_edges + nr) return;
   if (e >= n_edges) {                      // the diagonal of I, one entry per owned row
     uint64_t i = (uint64_t)(e - n_edges);
@@ -84,7 +84,7 @@ __global__ void k_make_keys(const int32_t* __restrict__ src, const int32_t* __re
 
 // ---- step 4: duplicate removal ------------------------------------------------------------------
 __global__ void k_flag_unique(const uint64_t* __restrict__ keys, int64_t m, uint32_t* __restrict__ flag) {
-  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t k = block_id() * blockDim.x + threadIdx.x;
   if (k >= m) return;
   uint64_t v = keys[k];
   flag[k] = (v != kInvalidKey && (k == 0 || keys[k - 1] != v)) ? 1u : 0u;
@@ -93,7 +93,7 @@ __global__ void k_flag_unique(const uint64_t* __restrict__ keys, int64_t m, uint
 __global__ void k_compact(const uint64_t* __restrict__ keys, const uint32_t* __restrict__ flag,
                           const int64_t* __restrict__ pos, int64_t m, int colbits,
                           uint64_t* __restrict__ ukeys, int32_t* __restrict__ col) {
-  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t k = block_id() * blockDim.x + threadIdx.x;
   if (k >= m || !flag[k]) return;
   uint64_t v = keys[k];
   int64_t p = pos[k];
@@ -105,7 +105,7 @@ __global__ void k_compact(const uint64_t* __restrict__ keys, const uint32_t* __r
 // of key[k] from `shift` upwards and are non-decreasing in k.  Requires n >= 1.
 __global__ void k_boundaries(const uint64_t* __restrict__ key, int64_t n, int shift, int64_t n_seg,
                              int64_t* __restrict__ ptr) {
-  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t k = block_id() * blockDim.x + threadIdx.x;
   if (k >= n) return;
   int64_t s = (int64_t)(key[k] >> shift);
   int64_t sp = k == 0 ? -1 : (int64_t)(key[k - 1] >> shift);
@@ -115,14 +115,14 @@ __global__ void k_boundaries(const uint64_t* __restrict__ key, int64_t n, int sh
 }
 
 __global__ void k_row_lengths(const int64_t* __restrict__ ptr, int64_t n, int32_t* __restrict__ len) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i < n) len[i] = (int32_t)(ptr[i + 1] - ptr[i]);
 }
 
 // first entry of each row whose (local) column is >= nr: columns are ascending, so the owned columns come first
 __global__ void k_row_mid(const int64_t* __restrict__ ptr, const int32_t* __restrict__ col, int64_t nr,
                           int64_t* __restrict__ mid) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i >= nr) return;
   int64_t lo = ptr[i], hi = ptr[i + 1];
   while (lo < hi) {
@@ -145,7 +145,7 @@ __global__ void k_values(const uint64_t* __restrict__ ukeys, int64_t nnz, int co
                          int64_t row_lo, const int32_t* __restrict__ deg_local,
                          const int32_t* __restrict__ deg_global, const int32_t* __restrict__ halo_gid,
                          float* __restrict__ val) {
-  int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t p = block_id() * blockDim.x + threadIdx.x;
   if (p >= nnz) return;
   uint64_t v = ukeys[p];
   int64_t i = (int64_t)(v >> colbits);
@@ -164,7 +164,7 @@ __global__ void k_values(const uint64_t* __restrict__ ukeys, int64_t nnz, int co
 // ---- step 6: column-major copy ------------------------------------------------------------------------
 __global__ void k_make_tkeys(const uint64_t* __restrict__ ukeys, int64_t nnz, int colbits,
                              uint64_t* __restrict__ tkeys, uint32_t* __restrict__ pay) {
-  int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t p = block_id() * blockDim.x + threadIdx.x;
   if (p >= nnz) return;
   uint64_t v = ukeys[p];
   uint64_t i = v >> colbits, c = v & ((1ull << colbits) - 1ull);
@@ -175,7 +175,7 @@ __global__ void k_make_tkeys(const uint64_t* __restrict__ ukeys, int64_t nnz, in
 __global__ void k_finish_csc(const uint64_t* __restrict__ tkeys, const uint32_t* __restrict__ pay,
                              const float* __restrict__ val, int64_t nnz, int32_t* __restrict__ rowidx,
                              float* __restrict__ val_t) {
-  int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t q = block_id() * blockDim.x + threadIdx.x;
   if (q >= nnz) return;
   rowidx[q] = (int32_t)(tkeys[q] & 0xffffffffull);
   val_t[q] = val[pay[q]];
@@ -184,7 +184,7 @@ __global__ void k_finish_csc(const uint64_t* __restrict__ tkeys, const uint32_t*
 // ---- schedules ------------------------------------------------------------------------------------------
 __global__ void k_sched_keys(const int64_t* __restrict__ ptr, int64_t n, uint64_t* __restrict__ keys,
                              uint32_t* __restrict__ hub_flag, uint32_t* __restrict__ hub_chunks) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i >= n) return;
   int64_t len = ptr[i + 1] - ptr[i];
   bool hub = len > kHubRowNnz;
@@ -196,7 +196,7 @@ __global__ void k_sched_keys(const int64_t* __restrict__ ptr, int64_t n, uint64_
 }
 
 __global__ void k_take_low32(const uint64_t* __restrict__ keys, int64_t n, int32_t* __restrict__ out) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i < n) out[i] = (int32_t)(keys[i] & 0xffffffffull);
 }
 
@@ -204,7 +204,7 @@ __global__ void k_hub_lists(const uint32_t* __restrict__ hub_flag, const int64_t
                             const uint32_t* __restrict__ hub_chunks, const int64_t* __restrict__ chunk_pos,
                             int64_t n, int64_t n_hub, int32_t* __restrict__ hub_rows,
                             int64_t* __restrict__ hub_chunk_ptr, int32_t* __restrict__ chunk_hub) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i >= n || !hub_flag[i]) return;
   int64_t h = hub_pos[i];
   hub_rows[h] = (int32_t)i;
@@ -448,6 +448,8 @@ extern "C" int gcn_csr_build(const int32_t* d_src, const int32_t* d_dst, int64_t
   *out = nullptr;
   if (n_edges < 0 || (n_edges > 0 && (!d_src || !d_dst))) return fail(GCN_EINVAL, "gcn_csr_build: bad edge list");
   if (n_global < 1 || n_global > 0x7fffffffLL) return fail(GCN_EINVAL, "gcn_csr_build: n_global must be in [1, 2^31)");
+  // entry positions travel through the sorts as 32-bit payloads
+  if (n_edges + n_global >= 0xffffffffLL) return fail(GCN_EINVAL, "gcn_csr_build: more than 2^32 - 1 edges and rows");
   if (row_lo < 0 || row_hi <= row_lo || row_hi > n_global) return fail(GCN_EINVAL, "gcn_csr_build: need 0 <= row_lo < row_hi <= n_global");
   if (!(row_lo == 0 && row_hi == n_global) && !d_deg_global)
     return fail(GCN_EINVAL, "gcn_csr_build: a block that is not the whole graph needs d_deg_global");

@@ -238,7 +238,7 @@ static int pick_vec(const void* p, int64_t ld, int64_t extent, size_t es) {
 template <typename T>
 static int gemm_nn_t(NnArgs& a, hipStream_t s) {
   const int64_t gm = ceil_div(a.M, BM);
-  if (gm > 0x7fffffffLL) return fail(GCN_EINVAL, "gemm: too many rows");
+  if (gm * 256 >= ((int64_t)1 << 32)) return fail(GCN_EINVAL, "gemm: too many rows for one launch");
   const double nb = (double)sizeof(T) * (double)a.M * (a.K + a.N * (a.C2 ? 2.0 : 1.0) + (a.mask ? a.N : 0)) +
                     4.0 * (double)a.K * a.N;
   ProfScope ps(GCN_K_GEMM_NN, s, a.N, sizeof(T) == 2 ? GCN_BF16 : GCN_F32, a.M, a.K, nb, nb,

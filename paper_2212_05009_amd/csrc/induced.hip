@@ -13,17 +13,17 @@
 namespace gcn {
 
 constexpr int kIndThreads = 256;
-static inline unsigned ind_grid(int64_t n) { return (unsigned)ceil_div(n > 0 ? n : 1, kIndThreads); }
+static inline dim3 ind_grid(int64_t n) { return fold_grid(ceil_div(n > 0 ? n : 1, kIndThreads)); }
 
 __global__ void k_ind_fill(int32_t* __restrict__ a, int64_t n, int32_t v) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i < n) a[i] = v;
 }
 
 // lid[vertices[k]] = k; ids out of range are reported, never used as an index
 __global__ void k_ind_scatter(const int32_t* __restrict__ vertices, int64_t n_sub, int64_t n,
                               int32_t* __restrict__ lid, int* __restrict__ bad) {
-  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t k = block_id() * blockDim.x + threadIdx.x;
   if (k >= n_sub) return;
   const int32_t v = vertices[k];
   if (v < 0 || v >= n) { *bad = 1; return; }
@@ -34,7 +34,7 @@ __global__ void k_ind_scatter(const int32_t* __restrict__ vertices, int64_t n_su
 // Also the number of stored entries of each selected row.
 __global__ void k_ind_rows(const int32_t* __restrict__ vertices, int64_t n_sub, const int32_t* __restrict__ lid,
                            const int64_t* __restrict__ rowptr, uint32_t* __restrict__ len, int* __restrict__ bad) {
-  int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t k = block_id() * blockDim.x + threadIdx.x;
   if (k >= n_sub) return;
   const int32_t v = vertices[k];
   if (lid[v] != (int32_t)k) *bad = 2;
@@ -44,7 +44,7 @@ __global__ void k_ind_rows(const int32_t* __restrict__ vertices, int64_t n_sub, 
 __global__ void k_ind_edges(const int32_t* __restrict__ vertices, int64_t n_sub, const int64_t* __restrict__ off,
                             int64_t total, const int64_t* __restrict__ rowptr, const int32_t* __restrict__ col,
                             const int32_t* __restrict__ lid, int32_t* __restrict__ src, int32_t* __restrict__ dst) {
-  int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t t = block_id() * blockDim.x + threadIdx.x;
   if (t >= total) return;
   int64_t lo = 0, hi = n_sub;                 // selected row k: the last one with off[k] <= t
   while (hi - lo > 1) {

@@ -3,6 +3,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "common.h"
 
 namespace gcn {
@@ -17,6 +19,10 @@ int fail(int code, const char* fmt, ...) {
   return code;
 }
 void clear_error() { g_err[0] = 0; }
+
+// most blocks in the x dimension of a launch: 2^22 blocks of up to 1024 threads stay below 2^32 threads
+static std::atomic<int64_t> g_max_grid_x{(int64_t)1 << 22};
+int64_t max_grid_x() { return g_max_grid_x.load(std::memory_order_relaxed); }
 
 typedef uint16_t bf16_t;
 
@@ -39,7 +45,7 @@ __global__ __launch_bounds__(256) void k_gather(const char* __restrict__ table, 
   typedef typename Unit<VB>::type U;
   constexpr int G = 256 / LPR;
   const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
-  const int64_t s = (int64_t)blockIdx.x * G + g;
+  const int64_t s = block_id() * G + g;
   if (s >= n_idx) return;
   const int64_t j = idx[s];
   const bool ok = j >= 0 && j < n_table_rows;
@@ -103,7 +109,7 @@ static bool is_host_memory(const void* p) {
 template <int VB>
 static int gather_v(const char* table, int64_t ldb, int64_t nt, int n_vec, const int32_t* idx, int64_t n_idx,
                     char* recv, int64_t ldrb, int d, int dtype, hipStream_t s) {
-  auto grid = [&](int lpr) { return dim3((unsigned)ceil_div(n_idx, 256 / lpr)); };
+  auto grid = [&](int lpr) { return fold_grid(ceil_div(n_idx, 256 / lpr)); };
   const double by = 2.0 * (double)n_idx * n_vec * VB + 4.0 * (double)n_idx;
   ProfScope ps(GCN_K_GATHER, s, d, dtype, n_idx, 0, by, by, 0.0);
   if (is_host_memory(table)) {
@@ -337,7 +343,7 @@ static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* 
 // dst[r][0 .. ld_dst) = src[r][0 .. d) followed by zeros: a copy with a padded leading dimension
 __global__ __launch_bounds__(256) void k_pad_rows(const char* __restrict__ src, int64_t ld_src, char* __restrict__ dst,
                                                   int64_t ld_dst, int64_t rows, int d, int es) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i >= rows * ld_dst) return;
   const int64_t r = i / ld_dst; const int c = (int)(i % ld_dst);
   if (es == 4) reinterpret_cast<uint32_t*>(dst)[i] = c < d ? reinterpret_cast<const uint32_t*>(src)[r * ld_src + c] : 0u;
@@ -350,13 +356,13 @@ int pad_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t
   const int64_t n = rows * ld_dst;
   const double by = (double)es * (double)rows * (double)(d + ld_dst);
   ProfScope ps(GCN_K_OTHER, s, d, dtype, rows, 0, by, by, 0.0);
-  k_pad_rows<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>((const char*)src, ld_src, (char*)dst, ld_dst, rows, d, es);
+  k_pad_rows<<<fold_grid(ceil_div(n, 256)), 256, 0, s>>>((const char*)src, ld_src, (char*)dst, ld_dst, rows, d, es);
   GCN_CHECK_LAUNCH();
   return GCN_OK;
 }
 
 __global__ __launch_bounds__(256) void k_sgd(float* __restrict__ W, const float* __restrict__ dW, int64_t n, float lr) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i < n) W[i] = fmaf(-lr, dW[i], W[i]);
 }
 
@@ -366,16 +372,23 @@ using namespace gcn;
 
 extern "C" const char* gcn_last_error(void) { return g_err; }
 
+extern "C" int gcn_debug_max_grid_x(int64_t blocks) {
+  clear_error();
+  if (blocks != 0 && (blocks < 1 || blocks > ((int64_t)1 << 22))) return fail(GCN_EINVAL, "gcn_debug_max_grid_x: need 0 (default) or 1 .. 2^22");
+  g_max_grid_x.store(blocks == 0 ? (int64_t)1 << 22 : blocks, std::memory_order_relaxed);
+  return GCN_OK;
+}
+
 extern "C" int gcn_sgd_update(float* W, const float* dW, int64_t n, float lr, void* stream) {
   clear_error();
   if (n < 0) return fail(GCN_EINVAL, "gcn_sgd_update: negative size");
   if (n == 0) return GCN_OK;
   if (!W || !dW) return fail(GCN_EINVAL, "gcn_sgd_update: NULL pointer");
-  if (n > 0x7fffffffLL * 256) return fail(GCN_EINVAL, "gcn_sgd_update: too many elements");
+  if (!grid_fits(ceil_div(n, 256))) return fail(GCN_EINVAL, "gcn_sgd_update: too many elements");
   hipStream_t s = (hipStream_t)stream;
   const double by = 12.0 * (double)n;
   ProfScope ps(GCN_K_OTHER, s, 1, GCN_F32, n, 0, by, by, 2.0 * (double)n);
-  k_sgd<<<(unsigned)ceil_div(n, 256), 256, 0, s>>>(W, dW, n, lr);
+  k_sgd<<<fold_grid(ceil_div(n, 256)), 256, 0, s>>>(W, dW, n, lr);
   GCN_CHECK_LAUNCH();
   return GCN_OK;
 }
@@ -388,7 +401,7 @@ extern "C" int gcn_halo_gather(const void* table, int64_t ld, int64_t n_table_ro
   if (dtype != GCN_F32 && dtype != GCN_BF16) return fail(GCN_EINVAL, "gcn_halo_gather: unknown dtype");
   if (n_idx == 0) return GCN_OK;
   if (!table || !d_idx || !recv) return fail(GCN_EINVAL, "gcn_halo_gather: NULL pointer");
-  if (n_idx > 0x7fffffffLL * 4) return fail(GCN_EINVAL, "gcn_halo_gather: index list too long");
+  if (!grid_fits(ceil_div(n_idx, 4))) return fail(GCN_EINVAL, "gcn_halo_gather: index list too long");
   const int64_t es = dtype == GCN_BF16 ? 2 : 4;
   const int64_t row_bytes = d * es, ldb = ld * es, ldrb = ldr * es;
   int vb = 16;

@@ -16,21 +16,21 @@
 namespace gcn {
 
 constexpr int kPsThreads = 256;
-static inline unsigned ps_grid(int64_t n) { return (unsigned)ceil_div(n > 0 ? n : 1, kPsThreads); }
+static inline dim3 ps_grid(int64_t n) { return fold_grid(ceil_div(n > 0 ? n : 1, kPsThreads)); }
 
 __global__ void k_ps_zero(int64_t* __restrict__ a, int64_t n) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i < n) a[i] = 0;
 }
 
 __global__ void k_ps_check(const int32_t* __restrict__ part, int64_t n, int p, int* __restrict__ bad) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i < n && (part[i] < 0 || part[i] >= p)) *bad = 1;
 }
 
 __global__ void k_ps_load(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ part, int64_t n,
                           int64_t* __restrict__ load) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t i = block_id() * blockDim.x + threadIdx.x;
   if (i >= n) return;
   atomicAdd(reinterpret_cast<unsigned long long*>(load + part[i]), (unsigned long long)(rowptr[i + 1] - rowptr[i]));
 }
@@ -38,7 +38,7 @@ __global__ void k_ps_load(const int64_t* __restrict__ rowptr, const int32_t* __r
 // entries whose ends share a part get the key of the pair id p*p, which sorts behind every real pair
 __global__ void k_ps_keys(const int64_t* __restrict__ rowptr, const int32_t* __restrict__ col, int64_t nnz, int64_t n,
                           const int32_t* __restrict__ part, int p, int jbits, uint64_t* __restrict__ keys) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t e = block_id() * blockDim.x + threadIdx.x;
   if (e >= nnz) return;
   int64_t lo = 0, hi = n;                  // row i: the last one with rowptr[i] <= e
   while (hi - lo > 1) {
@@ -53,7 +53,7 @@ __global__ void k_ps_keys(const int64_t* __restrict__ rowptr, const int32_t* __r
 
 __global__ void k_ps_flags(const uint64_t* __restrict__ keys, int64_t nnz, uint64_t first_invalid,
                            uint32_t* __restrict__ flag) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t e = block_id() * blockDim.x + threadIdx.x;
   if (e >= nnz) return;
   const uint64_t k = keys[e];
   flag[e] = k < first_invalid && (e == 0 || keys[e - 1] != k) ? 1u : 0u;
@@ -65,7 +65,7 @@ __global__ void k_ps_pairs(const uint64_t* __restrict__ keys, const int64_t* __r
                            int jbits, uint64_t first_invalid, int64_t* __restrict__ send_rows,
                            int64_t* __restrict__ recv_rows, int64_t* __restrict__ send_msgs,
                            int64_t* __restrict__ recv_msgs, int64_t* __restrict__ totals) {
-  int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t e = block_id() * blockDim.x + threadIdx.x;
   if (e >= nnz) return;
   const uint64_t k = keys[e];
   if (k >= first_invalid) return;

@@ -96,7 +96,7 @@ int exclusive_scan_u32(const uint32_t* in, int64_t* out, int64_t n, void* tmp, h
     return GCN_OK;
   }
   const int64_t nb = ceil_div(n, kScanTile);
-  if (nb > 0x7fffffffLL) return fail(GCN_EINVAL, "scan: input too large");
+  if (nb * kScanThreads >= ((int64_t)1 << 32)) return fail(GCN_EINVAL, "scan: input too large for one launch");
   int64_t* sums = (int64_t*)tmp;
   k_scan_reduce<<<dim3((unsigned)nb), dim3(kScanThreads), 0, s>>>(in, n, sums);
   k_scan_sums<<<dim3(1), dim3(kScanThreads), 0, s>>>(sums, nb, out + n);
@@ -216,7 +216,7 @@ int radix_sort_u64(uint64_t* keys_a, uint64_t* keys_b, uint32_t* pay_a, uint32_t
   uint32_t* pin = pay_a;  uint32_t* pout = pay_b;
   if (n > 0) {
     const int64_t nb = ceil_div(n, kSortTile);
-    if (nb > 0x7fffffffLL) return fail(GCN_EINVAL, "sort: input too large");
+    if (nb * kSortThreads >= ((int64_t)1 << 32)) return fail(GCN_EINVAL, "sort: input too large for one launch");
     const int64_t m = 256 * nb;
     char* p = (char*)tmp;
     uint32_t* hist = (uint32_t*)p;          p += align256(sizeof(uint32_t) * (size_t)m);

@@ -239,8 +239,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int g = lane / LPR, l = lane % LPR;
-  const int slice = (int)(blockIdx.x % (unsigned)a.S);
-  const int64_t item = blockIdx.x / (unsigned)a.S;
+  int slice; int64_t item;
+  if (gridDim.y == 1) {       // the usual case: 32-bit division
+    slice = (int)(blockIdx.x % (unsigned)a.S); item = blockIdx.x / (unsigned)a.S;
+  } else {
+    const int64_t bid = block_id();
+    slice = (int)(bid % a.S); item = bid / a.S;
+  }
   const int v_lo = slice * a.vps;
   const int v_hi = v_lo + a.vps < a.nvec ? v_lo + a.vps : a.nvec;
   __shared__ float part[4][TW];
@@ -318,7 +323,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_spmm_hub_finish(SpmmK a) {
   const int lane = threadIdx.x & 63;
   const int64_t tiles = (a.d + 63) / 64;
-  const int64_t wi = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int64_t wi = block_id() * 4 + (threadIdx.x >> 6);
   if (wi >= a.n_hub_rows * tiles) return;
   const int64_t h = wi / tiles;
   const int64_t f = (wi % tiles) * 64 + lane;
@@ -375,19 +380,19 @@ static int launch_l(SpmmK& k, const Schedule* sc, const SpmmProf& pf, bool narro
   if (k.n_bins == 0) { k.n_bins = 1; k.bin_wave_begin[0] = 0; k.bin_row_begin[0] = k.bin_row_end[0] = 0; k.bin_log2gr[0] = 0; }
   k.bin_wave_begin[k.n_bins] = waves;
   const int64_t blocks = (k.n_chunks + ceil_div(waves, 4)) * k.S;
-  if (blocks > 0x7fffffffLL) return fail(GCN_EINVAL, "spmm: too many rows for one launch");
+  if (!grid_fits(blocks)) return fail(GCN_EINVAL, "spmm: too many rows for one launch");
   if (blocks > 0) {
     ProfScope ps(pf.kind, s, k.d, pf.dtype, pf.rows, pf.nnz, pf.alg, pf.touched, pf.flops);
     // gathered vectors in flight per lane: 16 bytes each, 64 bytes in all
     constexpr int U = (int)(sizeof(T) * V) >= 16 ? 4 : 8;
-    if (narrow) k_spmm<T, V, LPR, U, true><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(k);
-    else k_spmm<T, V, LPR, U, false><<<dim3((unsigned)blocks), dim3(256), 0, s>>>(k);
+    if (narrow) k_spmm<T, V, LPR, U, true><<<fold_grid(blocks), dim3(256), 0, s>>>(k);
+    else k_spmm<T, V, LPR, U, false><<<fold_grid(blocks), dim3(256), 0, s>>>(k);
   }
   if (k.n_hub_rows > 0) {
     const double fb = 4.0 * (double)k.n_chunks * k.d + (double)sizeof(T) * (double)k.n_hub_rows * k.d;
     ProfScope ps(GCN_K_SPMM_FINISH, s, k.d, pf.dtype, k.n_hub_rows, k.n_chunks, fb, fb, (double)k.n_chunks * k.d);
     const int64_t fw = k.n_hub_rows * ceil_div(k.d, 64);
-    k_spmm_hub_finish<T><<<dim3((unsigned)ceil_div(fw, 4)), dim3(256), 0, s>>>(k);
+    k_spmm_hub_finish<T><<<fold_grid(ceil_div(fw, 4)), dim3(256), 0, s>>>(k);
   }
   GCN_CHECK_LAUNCH();
   return GCN_OK;

@@ -726,7 +726,7 @@ static bool panel_shape(const SpmmArgs& a, int* sw_out, int* lpg_out, int* ns_ou
   const size_t es = a.dtype == GCN_BF16 ? 2 : 4;
   // limits of the packed entry format and of 32-bit addressing of X
   const double xspan = (double)a.n_cols * (double)a.ldx * (double)es;
-  if (a.n_cols >= (1 << kColBits) - 1 || a.ldx * (int64_t)es >= (1 << 24) || xspan >= 4294967296.0 || a.nnz >= 0xffffffffLL)
+  if (a.n_cols >= (1 << kColBits) - 1 || a.ldx * (int64_t)es >= (1 << 24) || xspan >= 4294967296.0 || a.nnz >= 0xffffff00LL)      // (one thread per entry in the plan kernels: below 2^32 threads)
     return false;
   // the gathers are 16-byte vector loads
   auto aligned = [](const void* p, size_t al) { return ((uintptr_t)p % al) == 0; };
