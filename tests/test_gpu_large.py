@@ -303,3 +303,50 @@ def test_softmax_past_4gib(gcn, dev):
     base = torch.full((C,), scale / C, device=dev)
     assert torch.allclose(g0.sum(dim=1), torch.zeros(1, device=dev), atol=1e-9)
     assert torch.allclose(g0.gather(1, yy[:, None])[:, 0], (base[0] - scale).expand(g0.shape[0]), rtol=1e-5, atol=0)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Launches of more than 2^32 threads (2^24 blocks of 256): the runtime would run such a grid modulo 2^32 in one
+# dimension, the library folds it into two.  A graph without edges has A^ = I, so both products must return
+# their operand bit for bit, and a gather is a copy: closed forms that need no second copy of 35 GB on the host.
+def test_products_over_70m_rows_identity(gcn, dev):
+    import torch
+    n, d = 70_000_000, 128                     # two feature slices: n / 4 = 17.5 M blocks > 2^24
+    say(f"identity graph n={n} d={d}")
+    empty = torch.zeros(0, dtype=torch.int32, device=dev)
+    A = gcn.gcn_csr_build(empty, empty, n)
+    assert (A.nr, A.nh, A.nnz) == (n, 0, n)
+    arr = A.arrays()
+    for name, step in (("rowptr", 1), ("colptr", 1)):
+        t = arr[name]
+        assert int(t[0]) == 0 and int(t[-1]) == n and bool((t[1:] - t[:-1] == step).all()), name
+    for name in ("col", "rowidx"):
+        assert bool((arr[name] == torch.arange(n, dtype=torch.int32, device=dev)).all()), name
+    assert bool((arr["val"] == 1.0).all()) and bool((arr["deg"] == 1).all())
+    X = randn((n, d), dev, 31)
+    Y = torch.full((n, d), float("nan"), device=dev)
+    gcn.gcn_spmm(A, X, Y)
+    torch.cuda.synchronize()
+    for s in range(0, n, 1 << 22):
+        assert torch.equal(Y[s:s + (1 << 22)].view(torch.int32), X[s:s + (1 << 22)].view(torch.int32)), s
+    Y.fill_(float("nan"))
+    gcn.gcn_spmm_t(A, X, Y, epilogue=gcn.EPI_RELU)
+    torch.cuda.synchronize()
+    for s in range(0, n, 1 << 22):
+        assert torch.equal(Y[s:s + (1 << 22)], torch.clamp_min(X[s:s + (1 << 22)], 0.0)), s
+    A.free()
+
+
+def test_gather_of_135m_rows(gcn, dev):
+    import torch
+    nt, d, n_idx = 4096, 128, 135_000_000      # 8 rows per block: 16.9 M blocks > 2^24; 69 GB received
+    say(f"gather table={nt}x{d} n_idx={n_idx}")
+    table = randn((nt, d), dev, 37)
+    gen = torch.Generator(device=dev); gen.manual_seed(38)
+    idx = torch.randint(0, nt, (n_idx,), generator=gen, device=dev, dtype=torch.int32)
+    recv = torch.full((n_idx, d), float("nan"), device=dev)
+    gcn.gcn_halo_gather(table, idx, recv)
+    torch.cuda.synchronize()
+    for s in range(0, n_idx, 1 << 22):
+        e = min(n_idx, s + (1 << 22))
+        assert torch.equal(recv[s:e].view(torch.int32), table[idx[s:e].long()].view(torch.int32)), (s, e)
