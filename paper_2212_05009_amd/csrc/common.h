@@ -80,6 +80,25 @@ static inline dim3 fold_grid(int64_t blocks) {
 static inline bool grid_fits(int64_t blocks) { return blocks <= max_grid_x() * 65535; }
 #ifdef __HIPCC__
 __device__ __forceinline__ int64_t block_id() { return (int64_t)blockIdx.y * gridDim.x + blockIdx.x; }
+
+// bf16 features: a value is the upper half of the fp32 pattern.  Stores round to nearest even; NaN stays NaN.
+typedef uint16_t bf16_t;
+__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+// one element of a feature buffer of type T (float or bf16_t), widened to / rounded from fp32
+template <typename T> __device__ __forceinline__ float load_one(const T* p) {
+  if constexpr (sizeof(T) == 4) return (float)*p;
+  else return bf16_to_f32((bf16_t)*p);
+}
+template <typename T> __device__ __forceinline__ void store_one(T* p, float v) {
+  if constexpr (sizeof(T) == 4) *p = v;
+  else *p = f32_to_bf16(v);
+}
 #endif
 
 // ---- execution schedule of a compressed sparse matrix (row binning) ----------------------

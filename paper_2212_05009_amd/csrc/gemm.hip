@@ -14,22 +14,8 @@
 
 namespace gcn {
 
-typedef uint16_t bf16_t;
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-__device__ __forceinline__ float g_bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ __forceinline__ bf16_t g_f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
-template <typename T> __device__ __forceinline__ float ld(const T* p) {
-  if constexpr (sizeof(T) == 4) return (float)*p; else return g_bf16_to_f32((bf16_t)*p);
-}
-template <typename T> __device__ __forceinline__ void st(T* p, float v) {
-  if constexpr (sizeof(T) == 4) *p = v; else *p = g_f32_to_bf16(v);
-}
 
 constexpr int BM = 128;    // output rows per block (NN) / A-columns per block (TN)
 constexpr int BK = 16;     // reduction step
@@ -61,7 +47,7 @@ __device__ __forceinline__ void load4(const T* __restrict__ row, int64_t c, int6
     }
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) o[i] = (c + i < limit) ? ld<T>(row + c + i) : 0.f;
+  for (int i = 0; i < 4; ++i) o[i] = (c + i < limit) ? load_one<T>(row + c + i) : 0.f;
 }
 
 // 4 consecutive elements from a 16-byte (fp32) / 8-byte (bf16) aligned address, no bounds checks
@@ -208,17 +194,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
       for (int r = 0; r < 16; ++r) {
         const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
         keep[r] = 1.f;
-        if (Mk && m < a.mask_rows && m < a.M) keep[r] = ld<T>(Mk + m * a.ldmask + n);
+        if (Mk && m < a.mask_rows && m < a.M) keep[r] = load_one<T>(Mk + m * a.ldmask + n);
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t m = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
         if (m >= a.M) continue;
         float v = acc[i][j][r] + bias;
-        if (C2) st<T>(C2 + m * a.ldc2 + n, v);
+        if (C2) store_one<T>(C2 + m * a.ldc2 + n, v);
         if (a.relu) v = v > 0.f ? v : 0.f;
         v = keep[r] > 0.f ? v : 0.f;
-        st<T>(C + m * a.ldc + n, v);
+        store_one<T>(C + m * a.ldc + n, v);
       }
     }
 }
@@ -517,8 +503,8 @@ __global__ __launch_bounds__(256) void k_colsum_part(const T* __restrict__ G, in
     int64_t r = r0;
     for (; r + 16 <= r1; r += 16)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) ch[i] += ld<T>(G + (r + i) * ldg + c);
-    for (; r < r1; ++r) s += ld<T>(G + r * ldg + c);
+      for (int i = 0; i < 16; ++i) ch[i] += load_one<T>(G + (r + i) * ldg + c);
+    for (; r < r1; ++r) s += load_one<T>(G + r * ldg + c);
 #pragma unroll
     for (int i = 0; i < 16; ++i) s += ch[i];
     partial[(int64_t)blockIdx.x * N + c] = s;

@@ -19,7 +19,6 @@ namespace gcn {
 
 namespace {
 
-typedef uint16_t bf16_t;
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short short4v __attribute__((ext_vector_type(4)));
@@ -34,13 +33,6 @@ struct NnBf16Args {
 };
 
 constexpr int kThreads = 512;
-
-__device__ __forceinline__ bf16_t to_bf16(float f) {   // round to nearest even; NaN stays NaN
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
 
 // LV bf16 values per lane and k step: 8 -> one 16-byte request and a 16x16x32 MFMA, 4 -> 8 bytes and 16x16x16
 template <int LV> struct Frag;
@@ -93,7 +85,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 8))
         t = 2 * (n >> 5) + ((n & 7) >> 2);
         cc = 4 * ((n & 31) >> 3) + (n & 3);
       }
-      wl[(((s * NT + t) * 64 + q * 16 + cc) * LV) + el] = (k < a.K && n < a.N) ? to_bf16(a.W[(int64_t)k * a.ldw + n]) : (bf16_t)0;
+      wl[(((s * NT + t) * 64 + q * 16 + cc) * LV) + el] = (k < a.K && n < a.N) ? f32_to_bf16(a.W[(int64_t)k * a.ldw + n]) : (bf16_t)0;
     }
   }
   __syncthreads();
@@ -178,9 +170,9 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 8))
           v[r] = a.relu ? (pre[r] > 0.f ? pre[r] : 0.f) : pre[r];
           if constexpr (MASK) v[r] = kp[r] > 0.f ? v[r] : 0.f;
         }
-        out[t] = u32x2{(uint32_t)to_bf16(v[0]) | ((uint32_t)to_bf16(v[1]) << 16), (uint32_t)to_bf16(v[2]) | ((uint32_t)to_bf16(v[3]) << 16)};
+        out[t] = u32x2{(uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16), (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16)};
         if constexpr (SAVE)
-          out2[t] = u32x2{(uint32_t)to_bf16(pre[0]) | ((uint32_t)to_bf16(pre[1]) << 16), (uint32_t)to_bf16(pre[2]) | ((uint32_t)to_bf16(pre[3]) << 16)};
+          out2[t] = u32x2{(uint32_t)f32_to_bf16(pre[0]) | ((uint32_t)f32_to_bf16(pre[1]) << 16), (uint32_t)f32_to_bf16(pre[2]) | ((uint32_t)f32_to_bf16(pre[3]) << 16)};
       }
       if constexpr (kPair) {
 #pragma unroll

@@ -21,22 +21,8 @@
 
 namespace gcn {
 
-typedef uint16_t bf16_t;
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-template <typename T> __device__ __forceinline__ float ldg(const T* p) {
-  if constexpr (sizeof(T) == 4) return (float)*p; else return __uint_as_float((uint32_t)(*p) << 16);
-}
-template <typename T> __device__ __forceinline__ void stg(T* p, float f) {
-  if constexpr (sizeof(T) == 4) { *p = f; }
-  else {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) { *p = (T)((u >> 16) | 0x40u); return; }
-    u += 0x7fffu + ((u >> 16) & 1u);
-    *p = (T)(u >> 16);
-  }
-}
 
 // 4 consecutive elements starting at column k (multiple of 4) of a row, zero beyond `limit`
 template <typename T>
@@ -53,7 +39,7 @@ __device__ __forceinline__ void load_quad(const T* __restrict__ row, int k, int 
     return;
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) o[i] = (k + i < limit) ? ldg<T>(row + k + i) : 0.f;
+  for (int i = 0; i < 4; ++i) o[i] = (k + i < limit) ? load_one<T>(row + k + i) : 0.f;
 }
 
 // 4 consecutive elements starting at column n (multiple of 4) of a row, none beyond `limit`
@@ -65,7 +51,7 @@ __device__ __forceinline__ void store_quad(T* __restrict__ row, int n, int limit
     } else {
       bf16_t h[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) stg<T>(&h[i], v[i]);
+      for (int i = 0; i < 4; ++i) store_one<T>(&h[i], v[i]);
       uint2 pk;
       pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
       pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
@@ -75,7 +61,7 @@ __device__ __forceinline__ void store_quad(T* __restrict__ row, int n, int limit
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    if (n + i < limit) stg<T>(row + n + i, v[i]);
+    if (n + i < limit) store_one<T>(row + n + i, v[i]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -231,7 +217,7 @@ template <typename T> __device__ __forceinline__ void vstore4(T* __restrict__ p,
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     bf16_t h[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) stg<T>(&h[i], v[i]);
+    for (int i = 0; i < 4; ++i) store_one<T>(&h[i], v[i]);
     *reinterpret_cast<u32x2*>(p) = u32x2{(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
   }
 }
@@ -539,9 +525,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
         const T* __restrict__ ar = A + (k + 2 * u) * a.lda;
         const T* __restrict__ br = B + (k + 2 * u) * a.ldb;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) av[u][i] = ldg<T>(ar + aoff[i]);
+        for (int i = 0; i < TM; ++i) av[u][i] = load_one<T>(ar + aoff[i]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bv[u][j] = ldg<T>(br + boff[j]);
+        for (int j = 0; j < TN; ++j) bv[u][j] = load_one<T>(br + boff[j]);
       }
     } else {
 #pragma unroll
@@ -552,9 +538,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 8))) voi
         const T* __restrict__ ar = A + kc * a.lda;
         const T* __restrict__ br = B + kc * a.ldb;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) { const float v = ldg<T>(ar + aoff[i]); av[u][i] = rok ? v : 0.f; }
+        for (int i = 0; i < TM; ++i) { const float v = load_one<T>(ar + aoff[i]); av[u][i] = rok ? v : 0.f; }
 #pragma unroll
-        for (int j = 0; j < TN; ++j) { const float v = ldg<T>(br + boff[j]); bv[u][j] = rok ? v : 0.f; }
+        for (int j = 0; j < TN; ++j) { const float v = load_one<T>(br + boff[j]); bv[u][j] = rok ? v : 0.f; }
       }
     }
 #pragma unroll

@@ -24,8 +24,6 @@ void clear_error() { g_err[0] = 0; }
 static std::atomic<int64_t> g_max_grid_x{(int64_t)1 << 22};
 int64_t max_grid_x() { return g_max_grid_x.load(std::memory_order_relaxed); }
 
-typedef uint16_t bf16_t;
-
 // ------------------------------------------------------------------------------------------
 // Halo gather (Sec. 4.1: the rows of H selected by an index set are copied into the buffer of
 // received rows).  A row is moved as n_vec units of VB bytes; a group of LPR lanes owns a row,
@@ -144,19 +142,6 @@ static int gather_v(const char* table, int64_t ldb, int64_t nt, int n_vec, const
 constexpr int kLossBlocks = 4096;
 __device__ double g_loss_partial[kLossBlocks];
 
-template <typename T> __device__ __forceinline__ float ldf(const T* p) {
-  if constexpr (sizeof(T) == 4) return (float)*p; else return __uint_as_float((uint32_t)(*p) << 16);
-}
-template <typename T> __device__ __forceinline__ void stf(T* p, float f) {
-  if constexpr (sizeof(T) == 4) { *p = f; }
-  else {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) { *p = (T)((u >> 16) | 0x40u); return; }
-    u += 0x7fffu + ((u >> 16) & 1u);
-    *p = (T)(u >> 16);
-  }
-}
-
 template <typename T, int LPR>
 __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, int64_t ldz, int64_t nr, int C,
                                                       const int32_t* __restrict__ y, float scale,
@@ -169,13 +154,13 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, i
     T* go = G + row * ldg;
     const int label = y[row];
     if (label < 0 || label >= C) {                 // no label: no loss term, zero gradient
-      for (int c = l; c < C; c += LPR) stf<T>(go + c, 0.f);
+      for (int c = l; c < C; c += LPR) store_one<T>(go + c, 0.f);
       continue;
     }
     float mx = -INFINITY, se = 0.f;
     if (C <= LPR) {                      // one element per lane: one load, one exponential, one store
       const bool in = l < C;
-      const float zv = in ? ldf<T>(z + l) : -INFINITY;
+      const float zv = in ? load_one<T>(z + l) : -INFINITY;
       mx = zv;
 #pragma unroll
       for (int off = 1; off < LPR; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
@@ -183,25 +168,25 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, i
       se = ev;
 #pragma unroll
       for (int off = 1; off < LPR; off <<= 1) se += __shfl_xor(se, off, 64);
-      if (in) stf<T>(go + l, scale * (ev * (1.0f / se) - (l == label ? 1.f : 0.f)));
+      if (in) store_one<T>(go + l, scale * (ev * (1.0f / se) - (l == label ? 1.f : 0.f)));
       // the label's logit sits in lane `label` of this row's lane group: no second, dependent load
       const float zl = __shfl(zv, g * LPR + label, 64);
       if (l == 0) local += (double)(mx + logf(se)) - (double)zl;
       continue;
     } else {
-      for (int c = l; c < C; c += LPR) mx = fmaxf(mx, ldf<T>(z + c));
+      for (int c = l; c < C; c += LPR) mx = fmaxf(mx, load_one<T>(z + c));
 #pragma unroll
       for (int off = 1; off < LPR; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-      for (int c = l; c < C; c += LPR) se += expf(ldf<T>(z + c) - mx);
+      for (int c = l; c < C; c += LPR) se += expf(load_one<T>(z + c) - mx);
 #pragma unroll
       for (int off = 1; off < LPR; off <<= 1) se += __shfl_xor(se, off, 64);
       const float inv = 1.0f / se;
       for (int c = l; c < C; c += LPR) {
-        float p = expf(ldf<T>(z + c) - mx) * inv;
-        stf<T>(go + c, scale * (p - (c == label ? 1.f : 0.f)));
+        float p = expf(load_one<T>(z + c) - mx) * inv;
+        store_one<T>(go + c, scale * (p - (c == label ? 1.f : 0.f)));
       }
     }
-    if (l == 0) local += (double)(mx + logf(se)) - (double)ldf<T>(z + label);
+    if (l == 0) local += (double)(mx + logf(se)) - (double)load_one<T>(z + label);
   }
   // block sum in a fixed tree
   __shared__ double red[256];
@@ -260,7 +245,7 @@ __global__ __launch_bounds__(256) void k_softmax_xent_v4(const T* __restrict__ Z
       } else {
         T h[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) stf<T>(&h[i], o[i]);
+        for (int i = 0; i < 4; ++i) store_one<T>(&h[i], o[i]);
         uint2 pk;
         pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
         pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);

@@ -6,16 +6,6 @@
 
 namespace gcn {
 
-typedef uint16_t bf16_t;
-
-__device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {   // round to nearest even; NaN stays NaN
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
-
 template <typename T, int V> struct Vec;
 template <> struct Vec<float, 1> { typedef float type; };
 template <> struct Vec<float, 2> { typedef float2 type; };
@@ -34,15 +24,6 @@ __device__ __forceinline__ void load_vec(const T* __restrict__ p, float (&out)[V
     if constexpr (sizeof(T) == 4) out[i] = (float)e[i];
     else out[i] = bf16_to_f32((bf16_t)e[i]);
   }
-}
-
-template <typename T> __device__ __forceinline__ float load_one(const T* p) {
-  if constexpr (sizeof(T) == 4) return (float)*p;
-  else return bf16_to_f32((bf16_t)*p);
-}
-template <typename T> __device__ __forceinline__ void store_one(T* p, float v) {
-  if constexpr (sizeof(T) == 4) *p = v;
-  else *p = f32_to_bf16(v);
 }
 
 template <typename T, int V>
