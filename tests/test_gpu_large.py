@@ -33,6 +33,15 @@ def dev():
     return torch.device("cuda:0")
 
 
+@pytest.fixture(autouse=True)
+def release_cached_memory():
+    """The buffers here run to tens of GB; hand them back to the driver after each test, since the library
+    allocates its own workspaces outside the array library's pool."""
+    yield
+    import torch
+    torch.cuda.empty_cache()
+
+
 def randn(shape, dev, seed, dtype=None):
     import torch
     gen = torch.Generator(device=dev)
