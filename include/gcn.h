@@ -31,6 +31,9 @@
  *    builds an execution plan (a re-sorted copy of the matrix, 8 bytes per stored entry plus
  *    padding, kept in the handle until gcn_csr_free), which allocates and waits for the
  *    stream.  Later calls of that width class reuse the plan.
+ *  - Sizes: vertex ids and n_global lie below 2^31, edges + rows of a build below 2^32; dense buffers may
+ *    run past 2^32 bytes and 2^31 elements (row offsets are 64-bit).  A size that a kernel cannot take is
+ *    an error (GCN_EINVAL), never a truncated result.
  *  - Indices are int32, row/column pointers int64, matrix values and all accumulators fp32.
  *    dtype selects the element type of *feature* buffers: GCN_F32, or GCN_BF16 (bf16 storage,
  *    fp32 accumulation, round-to-nearest-even on store).
