@@ -595,3 +595,59 @@ def test_induced_subgraph_is_the_dense_submatrix():
     perm = np.random.default_rng(0).permutation(35)
     gp = oracle.graph_build(*oracle.induced_edges(src, dst, 35, perm), 35)
     assert np.array_equal(csr_to_dense(gp, gp.val), csr_to_dense(whole, whole.val)[np.ix_(perm, perm)])
+
+
+# ----------------------------------------------------------------------------- the tolerance bounds themselves
+@pytest.mark.parametrize("directed", [False, True])
+def test_bounds_are_the_sums_of_absolute_terms(directed):
+    """Every parity test allows tol * B, so a B that is too large would hollow out all of them: each bound the
+    oracle returns is the same sum with every factor replaced by its absolute value, written out densely here."""
+    n, lo, hi, d_in, d_out = 60, 10, 45, 7, 5
+    src, dst = rand_edges(n, 260, 41, directed)
+    whole = oracle.graph_build(src, dst, n)
+    g = oracle.graph_build(src, dst, n, lo, hi, deg_global=whole.deg)
+    assert g.nh > 0
+    M = np.abs(csr_to_dense(g, g.val.astype(np.float64)))            # |A^_m|, nr x nc
+    rng = np.random.default_rng(11)
+    H = rng.standard_normal((g.nc, d_in)).astype(np.float32)
+    W = rng.standard_normal((d_in, d_out)).astype(np.float32)
+    G = rng.standard_normal((g.nr, d_out)).astype(np.float32)
+    Zp = rng.standard_normal((g.nr, d_in)).astype(np.float32)
+    b = rng.standard_normal(d_out).astype(np.float32)
+    aH, aW, aG = (np.abs(x.astype(np.float64)) for x in (H, W, G))
+
+    f = oracle.layer_fwd(g, H, W, bias=b, act="relu")
+    np.testing.assert_allclose(f["Bz"], M @ aH @ aW + np.abs(b.astype(np.float64)), rtol=1e-12)
+
+    bw = oracle.layer_bwd(g, H, W, G, Zprev=Zp, want_dH=True, want_dbias=True)
+    np.testing.assert_allclose(bw["BdW"], (M @ aH).T @ aG, rtol=1e-12)
+    np.testing.assert_allclose(bw["Bdb"], aG.sum(0), rtol=1e-12)
+    BdH = M.T @ aG @ aW.T                                           # all nc rows, mask or no mask
+    keep = np.ones((g.nc, d_in), bool); keep[: g.nr] = Zp > 0
+    np.testing.assert_allclose(bw["BdH"][keep], BdH[keep], rtol=1e-12)
+    assert np.all(bw["BdH"] <= BdH * (1 + 1e-12))                   # a masked element may carry its bound or none
+    assert np.all(np.abs(bw["dW"]) <= bw["BdW"]) and np.all(np.abs(bw["dH"]) <= bw["BdH"] + 1e-300)
+
+    A = rng.standard_normal((13, 7)).astype(np.float32); B = rng.standard_normal((7, 5)).astype(np.float32)
+    aA, aB = np.abs(A.astype(np.float64)), np.abs(B.astype(np.float64))
+    for op, x, y in (("nn", A, B), ("nt", A, B.T.copy()), ("tn", A.T.copy(), B)):
+        _, Bd = oracle.gemm(op, x, y)
+        np.testing.assert_allclose(Bd, aA @ aB, rtol=1e-13)
+
+    Gall = rng.standard_normal((g.nc, d_out)).astype(np.float32)
+    pull = oracle.layer_bwd_pull(g, H[: g.nr], W, Gall, Zprev=Zp)
+    aGall = np.abs(Gall.astype(np.float64))
+    np.testing.assert_allclose(pull["BT"], M @ aGall, rtol=1e-12)
+    np.testing.assert_allclose(pull["BdH"], M @ aGall @ aW.T, rtol=1e-12)
+    np.testing.assert_allclose(pull["BdW"], aH[: g.nr].T @ (M @ aGall), rtol=1e-12)
+
+    Z = (3 * rng.standard_normal((g.nr, d_out))).astype(np.float32)
+    y = rng.integers(0, d_out, g.nr).astype(np.int32)
+    loss, labs, _ = oracle.softmax_xent(Z, y, 0.125)
+    Z64 = Z.astype(np.float64)
+    lse = np.log(np.exp(Z64 - Z64.max(1, keepdims=True)).sum(1)) + Z64.max(1)
+    zy = Z64[np.arange(g.nr), y]
+    assert abs(loss - 0.125 * (lse - zy).sum()) <= 1e-12 * labs
+    # the loss bound: at least the sum of the terms' magnitudes, at most a few times the largest logit per row
+    assert 0.125 * np.abs(lse - zy).sum() <= labs * (1 + 1e-12)
+    assert labs <= 0.125 * (3 * np.abs(Z64).max(1) + np.log(d_out)).sum() * (1 + 1e-12)
