@@ -52,6 +52,29 @@ static int64_t gather_ld_for(const gcn_csr* A, bool transposed, int d, int dtype
   return spmm_panel_wanted(probe) ? ld_line : ld;
 }
 
+// Average number of 128-byte lines that a row of `len` bytes touches when rows start at multiples of `pitch` bytes.
+static double lines_touched(int64_t pitch, int64_t len) {
+  int64_t g = 128;
+  while (pitch % g) g >>= 1;
+  double sum = 0.0;
+  for (int64_t o = 0; o < 128; o += g) sum += (double)((o + len + 127) / 128);
+  return sum / (double)(128 / g);
+}
+
+// A caller's operand [n_cols x d] with pitch ldx that a sparse product is about to gather: the pitch of a padded
+// copy worth making first, or ldx.  The copy moves every row once, the product reads a row per stored entry, so
+// it pays when there are several entries per column and the padded rows touch clearly fewer lines (bf16 width
+// 100: 200-byte rows at a pitch of 200 bytes touch 2.5 lines and admit 8-byte requests only; at 256 bytes 2 lines
+// and 16-byte requests).
+static int64_t padded_operand_ld(const gcn_csr* A, bool transposed, int d, int dtype, int64_t ldx) {
+  const int64_t es = (int64_t)es_of(dtype);
+  const int64_t ldp = gather_ld_for(A, transposed, d, dtype);
+  if (ldp == ldx) return ldx;
+  const int64_t n_cols = transposed ? A->nr : A->nc;
+  if (A->nnz < 8 * n_cols) return ldx;
+  return lines_touched(ldp * es, (int64_t)d * es) <= 0.85 * lines_touched(ldx * es, (int64_t)d * es) ? ldp : ldx;
+}
+
 struct Carver {              // hands out 256-byte aligned pieces of the workspace
   char* base; size_t used = 0;
   void* take(size_t bytes) { void* p = base ? base + used : nullptr; used += align256(bytes); return p; }
@@ -82,10 +105,14 @@ extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
     void* hub = ws.take(spmm_ws_bytes(&A->sched, sparse_first ? d_in : d_out));
     if (sparse_first) {
       void* AH = AH_save ? AH_save : ws.take((size_t)A->nr * d_in * es);
+      const int64_t ldhp = padded_operand_ld(A, false, d_in, dtype, ldh);
+      void* Hp = ldhp != ldh ? ws.take((size_t)A->nc * ldhp * es) : nullptr;
       if (pass) {
-        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, H, ldh, AH, d_in, nullptr, 0,
-                    d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+        if (Hp) GCN_TRY(pad_rows(H, ldh, Hp, ldhp, A->nc, d_in, dtype, s));
+        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, Hp ? Hp : H, Hp ? ldhp : ldh, AH, d_in,
+                    nullptr, 0, d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
         sp.owner = Am;
+        sp.x_rows_padded = Hp != nullptr;
         GCN_TRY(spmm_launch(sp, hub, s));
         GemmEpilogue epi;
         epi.bias = bias; epi.relu = relu; epi.C2 = Z; epi.ldc2 = d_out;

@@ -325,23 +325,39 @@ static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* 
   return GCN_OK;
 }
 
-// dst[r][0 .. ld_dst) = src[r][0 .. d) followed by zeros: a copy with a padded leading dimension
-__global__ __launch_bounds__(256) void k_pad_rows(const char* __restrict__ src, int64_t ld_src, char* __restrict__ dst,
-                                                  int64_t ld_dst, int64_t rows, int d, int es) {
+// dst[r][0 .. ld_dst) = src[r][0 .. d) followed by zeros: a copy with a padded leading dimension.  One thread moves
+// one unit of UB bytes; the widest unit that divides both pitches and the row length is used.
+template <typename U>
+__global__ __launch_bounds__(256) void k_pad_rows(const char* __restrict__ src, int64_t pitch_src, char* __restrict__ dst,
+                                                  int64_t pitch_dst, int64_t rows, int units_row, int units_dst) {
   const int64_t i = block_id() * blockDim.x + threadIdx.x;
-  if (i >= rows * ld_dst) return;
-  const int64_t r = i / ld_dst; const int c = (int)(i % ld_dst);
-  if (es == 4) reinterpret_cast<uint32_t*>(dst)[i] = c < d ? reinterpret_cast<const uint32_t*>(src)[r * ld_src + c] : 0u;
-  else reinterpret_cast<uint16_t*>(dst)[i] = c < d ? reinterpret_cast<const uint16_t*>(src)[r * ld_src + c] : (uint16_t)0;
+  if (i >= rows * units_dst) return;
+  const int64_t r = i / units_dst; const int c = (int)(i - r * units_dst);
+  U v;
+  if (c < units_row) v = reinterpret_cast<const U*>(src + r * pitch_src)[c];
+  else memset(&v, 0, sizeof(U));
+  reinterpret_cast<U*>(dst + r * pitch_dst)[c] = v;
 }
 
 int pad_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int d, int dtype, hipStream_t s) {
   if (rows <= 0) return GCN_OK;
-  const int es = dtype == GCN_BF16 ? 2 : 4;
-  const int64_t n = rows * ld_dst;
+  const int64_t es = dtype == GCN_BF16 ? 2 : 4;
+  const int64_t ps = ld_src * es, pd = ld_dst * es, len = (int64_t)d * es;
+  int ub = 16;
+  while (ub > es && !((ps % ub) == 0 && (pd % ub) == 0 && (len % ub) == 0 && ((uintptr_t)src % ub) == 0 &&
+                      ((uintptr_t)dst % ub) == 0)) ub >>= 1;
+  const int units_row = (int)(len / ub), units_dst = (int)(pd / ub);
+  const int64_t n = rows * units_dst;
   const double by = (double)es * (double)rows * (double)(d + ld_dst);
-  ProfScope ps(GCN_K_OTHER, s, d, dtype, rows, 0, by, by, 0.0);
-  k_pad_rows<<<fold_grid(ceil_div(n, 256)), 256, 0, s>>>((const char*)src, ld_src, (char*)dst, ld_dst, rows, d, es);
+  ProfScope ps_(GCN_K_OTHER, s, d, dtype, rows, 0, by, by, 0.0);
+  const dim3 grid = fold_grid(ceil_div(n, 256));
+  const char* sp = (const char*)src; char* dp = (char*)dst;
+  switch (ub) {
+    case 16: k_pad_rows<uint4><<<grid, 256, 0, s>>>(sp, ps, dp, pd, rows, units_row, units_dst); break;
+    case 8: k_pad_rows<uint2><<<grid, 256, 0, s>>>(sp, ps, dp, pd, rows, units_row, units_dst); break;
+    case 4: k_pad_rows<uint32_t><<<grid, 256, 0, s>>>(sp, ps, dp, pd, rows, units_row, units_dst); break;
+    default: k_pad_rows<uint16_t><<<grid, 256, 0, s>>>(sp, ps, dp, pd, rows, units_row, units_dst); break;
+  }
   GCN_CHECK_LAUNCH();
   return GCN_OK;
 }
