@@ -264,6 +264,54 @@ __global__ __launch_bounds__(256) void k_softmax_xent_v4(const T* __restrict__ Z
   if (threadIdx.x == 0) g_loss_partial[blockIdx.x] = red[0];
 }
 
+// Rows of up to 4 LPR classes that the vector form above cannot take (C no multiple of 4, or rows not aligned): a lane
+// holds the classes l, l + LPR, l + 2 LPR, l + 3 LPR, so a row is still read once and written once, and 64 / LPR rows
+// share a wavefront (C = 47: four rows per wavefront instead of one).
+template <typename T, int LPR>
+__global__ __launch_bounds__(256) void k_softmax_xent_s4(const T* __restrict__ Z, int64_t ldz, int64_t nr, int C,
+                                                         const int32_t* __restrict__ y, float scale,
+                                                         T* __restrict__ G, int64_t ldg) {
+  constexpr int GR = 256 / LPR;
+  const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
+  double local = 0.0;
+  for (int64_t row = (int64_t)blockIdx.x * GR + g; row < nr; row += (int64_t)gridDim.x * GR) {
+    const int label = y[row];
+    const bool labelled = label >= 0 && label < C;
+    const T* zr = Z + row * ldz;
+    float z[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) z[i] = l + LPR * i < C ? load_one<T>(zr + l + LPR * i) : -INFINITY;
+    float mx = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    float e[4], se = 0.f, zl = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      e[i] = l + LPR * i < C ? expf(z[i] - mx) : 0.f;
+      se += e[i];
+      if (l + LPR * i == label) zl = z[i];             // the label's logit, in one lane of the row
+    }
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) { se += __shfl_xor(se, off, 64); zl += __shfl_xor(zl, off, 64); }
+    const float inv = 1.0f / se;
+    T* gr = G + row * ldg;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = l + LPR * i;
+      if (c < C) store_one<T>(gr + c, labelled ? scale * (e[i] * inv - (c == label ? 1.f : 0.f)) : 0.f);
+    }
+    if (l == 0 && labelled) local += (double)(mx + logf(se)) - (double)zl;
+  }
+  __shared__ double red[256];
+  red[threadIdx.x] = local;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) g_loss_partial[blockIdx.x] = red[0];
+}
+
 // one block: thread t adds the partials t, t+256, ... in order, then a fixed tree over the threads
 __global__ __launch_bounds__(256) void k_loss_finish(int nblocks, float scale, float* __restrict__ loss) {
   __shared__ double red[256];
@@ -304,6 +352,24 @@ static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* 
       default: k_softmax_xent_v4<T, 64><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
     }
     k_loss_finish<<<1, 256, 0, s>>>(nb4, scale, loss);
+    GCN_CHECK_LAUNCH();
+    return GCN_OK;
+  }
+  if (C > 4 && C <= 256) {
+    int lp = 4;
+    while (4 * lp < C) lp <<= 1;
+    int64_t want_s = ceil_div(nr > 0 ? nr : 1, 256 / lp);
+    const int nbs = (int)(want_s < kLossBlocks ? want_s : kLossBlocks);
+    const double bys = (double)nr * (2.0 * sizeof(T) * C + 4.0);
+    ProfScope ps(GCN_K_SOFTMAX_XENT, s, C, sizeof(T) == 2 ? GCN_BF16 : GCN_F32, nr, 0, bys, bys, 0.0);
+    switch (lp) {
+      case 4: k_softmax_xent_s4<T, 4><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      case 8: k_softmax_xent_s4<T, 8><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      case 16: k_softmax_xent_s4<T, 16><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      case 32: k_softmax_xent_s4<T, 32><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      default: k_softmax_xent_s4<T, 64><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+    }
+    k_loss_finish<<<1, 256, 0, s>>>(nbs, scale, loss);
     GCN_CHECK_LAUNCH();
     return GCN_OK;
   }

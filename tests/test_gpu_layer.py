@@ -199,7 +199,7 @@ def test_layer_with_the_column_sweep(gcn, dev, er, hubs, directed_block, d_in, d
     run_bwd(gcn, dev, er, d_in, d_out, bf16=True)
 
 
-@pytest.mark.parametrize("C", [1, 2, 4, 8, 12, 16, 32, 41, 47, 64, 100, 256])
+@pytest.mark.parametrize("C", [1, 2, 3, 4, 5, 7, 8, 12, 16, 17, 32, 41, 47, 64, 65, 100, 130, 255, 256, 300])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_softmax_xent(gcn, dev, C, bf16):
     import torch
