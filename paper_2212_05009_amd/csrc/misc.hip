@@ -405,6 +405,18 @@ __global__ __launch_bounds__(256) void k_pad_rows(const char* __restrict__ src, 
   reinterpret_cast<U*>(dst + r * pitch_dst)[c] = v;
 }
 
+// the same for 2-byte elements whose source rows are only 2-byte aligned (odd pitch): a thread reads two elements
+// and writes one 4-byte word of the destination, whose pitch is even
+__global__ __launch_bounds__(256) void k_pad_rows_pairs(const uint16_t* __restrict__ src, int64_t ld_src, uint32_t* __restrict__ dst,
+                                                        int64_t words_dst, int64_t rows, int d) {
+  const int64_t i = block_id() * blockDim.x + threadIdx.x;
+  if (i >= rows * words_dst) return;
+  const int64_t r = i / words_dst; const int c = 2 * (int)(i - r * words_dst);
+  const uint16_t* sr = src + r * ld_src;
+  const uint32_t lo = c < d ? sr[c] : 0u, hi = c + 1 < d ? sr[c + 1] : 0u;
+  dst[i] = lo | (hi << 16);
+}
+
 int pad_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int d, int dtype, hipStream_t s) {
   if (rows <= 0) return GCN_OK;
   const int64_t es = dtype == GCN_BF16 ? 2 : 4;
@@ -416,8 +428,14 @@ int pad_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t
   const int64_t n = rows * units_dst;
   const double by = (double)es * (double)rows * (double)(d + ld_dst);
   ProfScope ps_(GCN_K_OTHER, s, d, dtype, rows, 0, by, by, 0.0);
-  const dim3 grid = fold_grid(ceil_div(n, 256));
   const char* sp = (const char*)src; char* dp = (char*)dst;
+  if (ub == 2 && (ld_dst % 2) == 0 && ((uintptr_t)dst % 4) == 0) {
+    const int64_t words = ld_dst / 2;
+    k_pad_rows_pairs<<<fold_grid(ceil_div(rows * words, 256)), 256, 0, s>>>((const uint16_t*)src, ld_src, (uint32_t*)dst, words, rows, d);
+    GCN_CHECK_LAUNCH();
+    return GCN_OK;
+  }
+  const dim3 grid = fold_grid(ceil_div(n, 256));
   switch (ub) {
     case 16: k_pad_rows<uint4><<<grid, 256, 0, s>>>(sp, ps, dp, pd, rows, units_row, units_dst); break;
     case 8: k_pad_rows<uint2><<<grid, 256, 0, s>>>(sp, ps, dp, pd, rows, units_row, units_dst); break;
