@@ -1,6 +1,7 @@
 """Helpers shared by the GPU parity tests."""
 from __future__ import annotations
 
+import os
 import sys
 
 import numpy as np
@@ -29,6 +30,10 @@ def check_bound(gpu, ref, bound, tol=TOL_F32, what=""):
         raise AssertionError(f"{what}: {bad.sum()} of {bad.size} elements outside {tol:g}*sum|terms|; worst at {k}: "
                              f"gpu={gpu[k]!r} ref={ref[k]!r} err={err[k]:.3e} limit={lim[k]:.3e}")
     ratio = np.max(err / np.maximum(lim, 1e-300)) if err.size else 0.0
+    log = os.environ.get("GCN_TEST_RATIO_LOG")      # optional record of how much of each tolerance was used
+    if log:
+        with open(log, "a") as f:
+            f.write(f"{tol:g}\t{float(ratio):.4f}\t{what}\n")
     return float(ratio)
 
 
