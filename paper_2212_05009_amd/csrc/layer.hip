@@ -195,6 +195,9 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
       const int64_t ldq = gather_ld_for(A, true, d_in, dtype);
       void* Q = dH ? ws.take((size_t)A->nr * ldq * es) : nullptr;
       void* AH = AH_saved ? nullptr : ws.take((size_t)A->nr * ldq * es);
+      // the product A^ H gathers the caller's H: from a padded copy where that saves line reads, as in the forward pass
+      const int64_t ldhp = AH_saved ? ldh : padded_operand_ld(A, false, d_in, dtype, ldh);
+      void* Hp = ldhp != ldh ? ws.take((size_t)A->nc * ldhp * es) : nullptr;
       void* tn = ws.take(gemm_tn_ws_bytes(A->nr, d_in, d_out));
       if (pass) {
         if (dH) {
@@ -209,9 +212,11 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
         }
         const void* ah = AH_saved; int64_t ldah = d_in;
         if (!AH_saved) {
-          SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, H, ldh, AH, ldq, nullptr, 0,
-                      d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+          if (Hp) GCN_TRY(pad_rows(H, ldh, Hp, ldhp, A->nc, d_in, dtype, s));
+          SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, Hp ? Hp : H, Hp ? ldhp : ldh, AH, ldq,
+                      nullptr, 0, d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
           sp.owner = Am;
+          sp.x_rows_padded = Hp != nullptr;
           GCN_TRY(spmm_launch(sp, hub, s));
           ah = AH; ldah = ldq;
         }
