@@ -158,6 +158,12 @@ int gcn_halo_gather(const void* table, int64_t ld, int64_t n_table_rows, int d, 
 int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W,
                   const float* bias, int d_in, int d_out, int act, int dtype, void* Z, void* Hout,
                   void* AH_save, void* stream);
+/* The same layer (Sec. 3.1 first equation, Sec. 4.1) with a leading dimension for every feature buffer, so that a
+ * layer's output can be written straight into a buffer with the pitch the next layer's sparse product gathers
+ * best from (gcn_feature_ld): Z (ldz), Hout (ldo), AH_save (ldah), each >= its row width. */
+int gcn_layer_fwd_ld(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W, const float* bias, int d_in,
+                     int d_out, int act, int dtype, void* Z, int64_t ldz, void* Hout, int64_t ldo, void* AH_save,
+                     int64_t ldah, void* stream);
 
 /*
  * Backward pass of one layer on the block (Sec. 3.1 second and third equations, Sec. 4.2):
@@ -174,6 +180,11 @@ int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W
 int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, const void* AH_saved,
                   const float* W, int d_in, int d_out, int dtype, const void* G,
                   const void* Zprev, float* dW, float* dbias, void* dH, void* stream);
+/* The same backward pass (Sec. 3.1 second and third equations, Sec. 4.2) with a leading dimension for every
+ * feature buffer: AH_saved (ldah), G (ldg), Zprev (ldzp), dH (lddh), each >= its row width. */
+int gcn_layer_bwd_ld(const gcn_csr_t* A, const void* H, int64_t ldh, const void* AH_saved, int64_t ldah,
+                     const float* W, int d_in, int d_out, int dtype, const void* G, int64_t ldg, const void* Zprev,
+                     int64_t ldzp, float* dW, float* dbias, void* dH, int64_t lddh, void* stream);
 
 /*
  * Output-layer loss and gradient (Sec. 3.1: G^L = grad J (.) act'(Z^L), identity activation on
@@ -323,6 +334,15 @@ int gcn_profile_filter(int kind_mask, int d);
 int64_t gcn_profile_count(int64_t* dropped);
 int gcn_profile_get(int64_t i, gcn_profile_rec* out);
 
+/* ---- row pitch the sparse products gather best from -----------------------------------------------
+ * Every dense argument carries its own leading dimension, and any pitch >= d works.  What the gathers of
+ * gcn_spmm / gcn_spmm_t (and the layer calls built on them) run fastest from is rows that start on a 128-byte
+ * line with a pitch of an ODD number of lines: the feature dimension is then worked on in slices of one line per
+ * group of compute units (Sec. 4.1's per-row task, split over the feature dimension), and an odd pitch spreads the
+ * lines of one slice over all cache and memory channels.  Returns that pitch in elements for rows of d elements of
+ * dtype (d itself for rows of at most one line), or -1 for a bad argument.  Pure host arithmetic. */
+int64_t gcn_feature_ld(int d, int dtype);
+
 /* ---- launch geometry (a test hook) -------------------------------------------------------------
  * Kernels whose grid grows with the problem size are launched with at most 2^22 blocks in the grid's x
  * dimension and the rest in y, because a launch whose x extent reaches 2^32 threads is not refused by the
@@ -331,6 +351,19 @@ int gcn_profile_get(int64_t i, gcn_profile_rec* out);
  * not depend on it.  With a bound b, a call whose kernel would need more than 65535 b blocks returns
  * GCN_EINVAL.  Not thread-safe against launches in flight on other host threads. */
 int gcn_debug_max_grid_x(int64_t blocks);
+
+/* ---- kernel-selection overrides (a test and experiment hook) -----------------------------------
+ * The library picks kernels and launch shapes by rules of its own.  Each rule can be overridden through an
+ * environment variable, read ONCE per process when the library first consults any of them, or afterwards through
+ * this call (name = the variable's name, e.g. "GCN_SPMM_PANEL"; value = what the variable would hold;
+ * GCN_TUNE_DEFAULT restores the built-in default).  Names: GCN_SPMM_PANEL (0 never / 1 always use the column
+ * sweep; default by heuristic, -1), GCN_PANEL_NARROW, GCN_PANEL_NOSYNC, GCN_PANEL_VERBOSE, GCN_SPMM_SLICES
+ * (1, 2, 4, 8; 0 = by rule), GCN_SPMM_EPG, GCN_SPMM_WIDE, GCN_GEMM_DIRECT, GCN_GEMM_FAST, GCN_GEMM_TN_WIDE,
+ * GCN_GEMM_BF16 (0 = that kernel family off), GCN_GEMM_TN_BLOCKS, GCN_GATHER_HOST_BLOCKS.  No override changes
+ * what is computed.  Returns GCN_EINVAL for an unknown name or a value out of range.  Process-wide and not
+ * thread-safe against calls in flight on other host threads. */
+#define GCN_TUNE_DEFAULT (-2147483647 - 1)
+int gcn_debug_set_tuning(const char* name, int value);
 
 #ifdef __cplusplus
 }

@@ -52,6 +52,12 @@ def _load():
     lib.gcn_halo_gather.argtypes = [vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, C.c_int64, vp, C.c_int64, vp]
     lib.gcn_layer_fwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]
     lib.gcn_layer_bwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp]
+    lib.gcn_layer_fwd_ld.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_int64, vp, C.c_int64,
+                                     vp, C.c_int64, vp]
+    lib.gcn_layer_fwd_ld.restype = C.c_int
+    lib.gcn_layer_bwd_ld.argtypes = [vp, vp, C.c_int64, vp, C.c_int64, vp, C.c_int, C.c_int, C.c_int, vp, C.c_int64, vp, C.c_int64,
+                                     vp, vp, vp, C.c_int64, vp]
+    lib.gcn_layer_bwd_ld.restype = C.c_int
     lib.gcn_softmax_xent.argtypes = [vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, C.c_float, vp, vp, C.c_int64, vp]
     lib.gcn_spmm_part.argtypes = [vp, C.c_int, vp, C.c_int64, C.c_int, C.c_int, vp, C.c_int64, C.c_int, vp, vp, C.c_int64, vp]
     lib.gcn_spmm_part.restype = C.c_int
@@ -75,6 +81,10 @@ def _load():
     lib.gcn_profile_get.restype = C.c_int
     lib.gcn_debug_max_grid_x.argtypes = [C.c_int64]
     lib.gcn_debug_max_grid_x.restype = C.c_int
+    lib.gcn_feature_ld.argtypes = [C.c_int, C.c_int]
+    lib.gcn_feature_ld.restype = C.c_int64
+    lib.gcn_debug_set_tuning.argtypes = [C.c_char_p, C.c_int]
+    lib.gcn_debug_set_tuning.restype = C.c_int
     for name in ("gcn_csr_build", "gcn_csr_info", "gcn_csr_arrays", "gcn_csr_free", "gcn_spmm", "gcn_spmm_t",
                  "gcn_halo_gather", "gcn_layer_fwd", "gcn_layer_bwd", "gcn_softmax_xent"):
         getattr(lib, name).restype = C.c_int
@@ -332,6 +342,55 @@ def gcn_layer_bwd(A: Csr, H: torch.Tensor, W: torch.Tensor, G: torch.Tensor, dW:
     return dW
 
 
+def _pitched(t, rows, cols, dtype, what):
+    """(pointer, ld) of a [rows, cols] tensor with contiguous rows and any row pitch; (None, 0) for None."""
+    if t is None:
+        return None, 0
+    ld, c = _rowmajor(_dev(t, dtype, what), what)
+    if t.shape[0] != rows or c != cols:
+        raise TypeError(f"{what} must be [{rows}, {cols}]")
+    return _ptr(t), ld
+
+
+def gcn_layer_fwd_ld(A: Csr, H: torch.Tensor, W: torch.Tensor, Hout: torch.Tensor, act: int = ACT_RELU,
+                     bias: torch.Tensor | None = None, Z: torch.Tensor | None = None, AH_save: torch.Tensor | None = None):
+    """gcn_layer_fwd for feature tensors of any row pitch (e.g. feature_buffer views)."""
+    ldh, d_in = _rowmajor(_dev(H), "H")
+    if H.shape[0] != A.nc:
+        raise TypeError("gcn_layer_fwd_ld: H must have nc rows")
+    d_out = W.shape[1]
+    _dense(W, d_in, d_out, torch.float32, "W")
+    po, ldo = _pitched(Hout, A.nr, d_out, H.dtype, "Hout")
+    pz, ldz = _pitched(Z, A.nr, d_out, H.dtype, "Z")
+    pa, ldah = _pitched(AH_save, A.nr, d_in, H.dtype, "AH_save")
+    if bias is not None:
+        _dense(bias.view(1, -1), 1, d_out, torch.float32, "bias")
+    _check(_lib.gcn_layer_fwd_ld(A.handle, _ptr(H), ldh, _ptr(W), _ptr(bias), d_in, d_out, act, _dtype_code(H), pz, ldz,
+                                 po, ldo, pa, ldah, _stream()), "gcn_layer_fwd_ld")
+    return Hout
+
+
+def gcn_layer_bwd_ld(A: Csr, H: torch.Tensor, W: torch.Tensor, G: torch.Tensor, dW: torch.Tensor,
+                     dH: torch.Tensor | None = None, Zprev: torch.Tensor | None = None,
+                     AH_saved: torch.Tensor | None = None, dbias: torch.Tensor | None = None):
+    """gcn_layer_bwd for feature tensors of any row pitch."""
+    ldh, d_in = _rowmajor(_dev(H), "H")
+    if H.shape[0] != A.nc:
+        raise TypeError("gcn_layer_bwd_ld: H must have nc rows")
+    d_out = W.shape[1]
+    _dense(W, d_in, d_out, torch.float32, "W")
+    _dense(dW, d_in, d_out, torch.float32, "dW")
+    pg, ldg = _pitched(G, A.nr, d_out, H.dtype, "G")
+    pd, lddh = _pitched(dH, A.nc, d_in, H.dtype, "dH")
+    pz, ldzp = _pitched(Zprev, A.nr, d_in, H.dtype, "Zprev")
+    pa, ldah = _pitched(AH_saved, A.nr, d_in, H.dtype, "AH_saved")
+    if dbias is not None:
+        _dense(dbias.view(1, -1), 1, d_out, torch.float32, "dbias")
+    _check(_lib.gcn_layer_bwd_ld(A.handle, _ptr(H), ldh, pa, ldah, _ptr(W), d_in, d_out, _dtype_code(H), pg, ldg,
+                                 pz, ldzp, _ptr(dW), _ptr(dbias), pd, lddh, _stream()), "gcn_layer_bwd_ld")
+    return dW
+
+
 def gcn_layer_bwd_pull(A: Csr, H: torch.Tensor, W: torch.Tensor, G: torch.Tensor, T: torch.Tensor, dW: torch.Tensor,
                        dH: torch.Tensor | None = None, Zprev: torch.Tensor | None = None,
                        dbias: torch.Tensor | None = None, phase: int = 0):
@@ -387,6 +446,27 @@ def gcn_sgd_update(W: torch.Tensor, dW: torch.Tensor, lr: float):
 def gcn_debug_max_grid_x(blocks: int):
     """Test hook: most blocks in the x dimension of a launch (0 restores the default of 2^22)."""
     _check(_lib.gcn_debug_max_grid_x(int(blocks)), "gcn_debug_max_grid_x")
+
+
+def gcn_feature_ld(d: int, dtype: torch.dtype = torch.float32) -> int:
+    """Row pitch (elements) the sparse products gather best from for rows of d elements."""
+    ld = int(_lib.gcn_feature_ld(int(d), BF16 if dtype == torch.bfloat16 else F32))
+    if ld < 0:
+        raise GcnError("gcn_feature_ld: bad argument")
+    return ld
+
+
+def feature_buffer(rows: int, d: int, dtype: torch.dtype = torch.float32, device=None) -> torch.Tensor:
+    """An uninitialised [rows, d] view of a buffer whose row pitch is gcn_feature_ld(d, dtype) (allocation only)."""
+    return torch.empty(rows, gcn_feature_ld(d, dtype), dtype=dtype, device=device)[:, :d]
+
+
+TUNE_DEFAULT = -2147483648
+
+
+def gcn_debug_set_tuning(name: str, value: int | None):
+    """Test and experiment hook: override one kernel-selection rule (value None restores the default)."""
+    _check(_lib.gcn_debug_set_tuning(name.encode(), TUNE_DEFAULT if value is None else int(value)), "gcn_debug_set_tuning")
 
 
 def gcn_profile_enable(on: bool):

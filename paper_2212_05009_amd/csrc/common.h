@@ -29,6 +29,24 @@ void clear_error();
 
 #define GCN_CHECK_LAUNCH() GCN_HIP(hipGetLastError())
 
+// ---- overrides for experiments and tests ---------------------------------------------------------
+// Each field starts from the environment variable of the same name in upper case with the prefix GCN_ (read
+// once, when the library first needs any of them); gcn_debug_set_tuning() changes a field afterwards.  None
+// changes what is computed, only which kernel or launch shape computes it.
+struct Tuning {
+  int spmm_panel = -1;          // column sweep: -1 by heuristic, 0 never, 1 wherever its plan can be built
+  int panel_narrow = 0;         // column sweep: 8-lane groups even where half-wavefront groups apply
+  int panel_nosync = 0;         // column sweep: drop the per-column-block waits
+  int panel_verbose = 0;        // column sweep: print the plan chosen
+  int spmm_slices = 0;          // feature slices of the row kernel (0: by rule)
+  int spmm_epg = 0;             // entries per lane group before a row is shared by more groups (0: default)
+  int spmm_wide = 0;            // 64-bit gather addresses even where 32 bits suffice
+  int gemm_direct = 1, gemm_fast = 1, gemm_tn_wide = 1, gemm_bf16 = 1;   // 0 switches a dense kernel family off
+  int gemm_tn_blocks = 512;     // blocks the A^T B kernel aims for
+  int gather_host_blocks = 32;  // workgroups of the host-table gather
+};
+const Tuning& tune();
+
 // ---- optional per-kernel timing (profile.hip) ------------------------------------------------
 // Put one on the stack around a kernel launch: records a start event now and a stop event when it
 // goes out of scope, both on `s`, if profiling is enabled; otherwise costs one relaxed load.

@@ -210,8 +210,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
 }
 
 static bool use_direct() {
-  const char* e = getenv("GCN_GEMM_DIRECT");      // override for experiments: 0 = LDS-tiled kernels only
-  return !(e && e[0] == '0');
+  return tune().gemm_direct != 0;      // override for experiments: 0 = LDS-tiled kernels only
 }
 
 static int pick_vec(const void* p, int64_t ld, int64_t extent, size_t es) {

@@ -402,7 +402,7 @@ static bool wide_requests(const void* A, int64_t lda, int K) {
 }
 
 bool gemm_nn_bf16_ok(const void* A, int64_t lda, void* C, int64_t ldc, int64_t M, int N, int K, const GemmEpilogue& epi) {
-  static const bool off = getenv("GCN_GEMM_BF16") && atoi(getenv("GCN_GEMM_BF16")) == 0;
+  const bool off = tune().gemm_bf16 == 0;
   if (off || M < 1 || N < 1 || N > 256 || K < 1) return false;
   const int NT = nn_tiles_bf16(N);
   const bool wide = wide_requests(A, lda, K);
@@ -434,7 +434,7 @@ int gemm_nn_bf16(const void* A, int64_t lda, const float* W, int64_t ldw, void* 
 }
 
 bool gemm_tn_bf16_ok(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N) {
-  static const bool off = getenv("GCN_GEMM_BF16") && atoi(getenv("GCN_GEMM_BF16")) == 0;
+  const bool off = tune().gemm_bf16 == 0;
   if (off || Kd < 1 || M < 1 || N < 1) return false;
   if ((lda % 4) != 0 || ((uintptr_t)A % 8) != 0) return false;
   if (N > 32 && ((ldb % 2) != 0 || ((uintptr_t)B % 4) != 0)) return false;

@@ -422,7 +422,7 @@ static int nn_launch_fast(const NnDirectArgs& a, hipStream_t s) {
 // the branch-free kernel serves aligned rows with K up to 128 or a multiple of 128
 template <typename T>
 static bool nn_fast(const NnDirectArgs& a, hipStream_t s, int* rc) {
-  static const bool off = getenv("GCN_GEMM_FAST") && atoi(getenv("GCN_GEMM_FAST")) == 0;
+  const bool off = tune().gemm_fast == 0;
   const int NT = nn_tiles(a.N);
   if (off || a.vecA != 4 || a.vecC != 4 || (a.C2 && a.vecC2 != 4)) return false;
   if (a.mask && (a.vecM != 4 || a.mask_rows < a.M || a.C2)) return false;
@@ -762,7 +762,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 8))) voi
 constexpr int kWideUK1 = 8, kWideUK2 = 8;   // row pairs per request batch (TN = 1, TN = 2)
 
 static bool tn_wide_ok(const void* A, int64_t lda, const void* B, int64_t ldb, int N, int dtype) {
-  static const bool off = getenv("GCN_GEMM_TN_WIDE") && atoi(getenv("GCN_GEMM_TN_WIDE")) == 0;
+  const bool off = tune().gemm_tn_wide == 0;
   const size_t es = dtype == GCN_BF16 ? 2 : 4;
   if (off || (lda % 4) != 0 || ((uintptr_t)A % (4 * es)) != 0) return false;
   if (lda >= (1 << 28) || ldb >= (1 << 28)) return false;      // a lane's offset (one row + a column, in bytes) is kept in 32 bits
@@ -775,7 +775,7 @@ int tn_wide_wn(int N) { return N <= 64 ? 1 : N <= 128 ? 2 : 4; }
 
 // splits of the vector variant: about two blocks per compute unit
 int tn_wide_splits(int64_t Kd, int M, int N) {
-  static const int blocks = [] { const char* e = getenv("GCN_GEMM_TN_BLOCKS"); const int v = e ? atoi(e) : 0; return v > 0 ? v : 512; }();
+  const int blocks = tune().gemm_tn_blocks;
   const int64_t tiles = ceil_div(M, 128) * ceil_div(N, (N <= 32 ? 32 : 64) * tn_wide_wn(N));
   int64_t want = ceil_div(blocks, tiles);
   int64_t max_by_k = ceil_div(Kd, 512);

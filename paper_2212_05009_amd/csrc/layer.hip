@@ -38,10 +38,25 @@ static int64_t gather_ld(int d, size_t es) {
 // transposed copy where `transposed`).  The column sweep asks for a row in slices of 128 bytes, one request per
 // slice: a slice that straddles two lines costs two line reads, so rows longer than a line then start on a line
 // (measured, fp32 width 41 over 233 k rows with 490 entries each: pitch 192 bytes 2.29 ms, 256 bytes 1.91 ms).
+//
+// Operands large enough for the row kernel to work in feature slices (spmm.hip: one 128-byte line per slice and
+// group of compute units) get gcn_feature_ld's pitch: rows on lines, an odd number of lines apart.
 static int64_t gather_ld_for(const gcn_csr* A, bool transposed, int d, int dtype) {
   const int64_t es = (int64_t)es_of(dtype);
   const int64_t ld = gather_ld(d, (size_t)es), ld_line = round_up((int64_t)d * es, 128) / es;
-  if (ld_line == ld || (int64_t)d * es <= 128) return ld;
+  if ((int64_t)d * es <= 128) return ld;
+  const int64_t n_cols = transposed ? A->nr : A->nc;
+  if ((double)n_cols * (double)d * (double)es > 16e6 && tune().spmm_panel != 1) {
+    SpmmArgs probe0{};
+    probe0.owner = const_cast<gcn_csr*>(A);
+    probe0.transposed = transposed;
+    probe0.n_rows = transposed ? A->nc : A->nr;
+    probe0.n_cols = n_cols;
+    probe0.nnz = A->nnz; probe0.d = d; probe0.dtype = dtype;
+    probe0.X = reinterpret_cast<const void*>((uintptr_t)256); probe0.ldx = ld_line; probe0.x_rows_padded = true;
+    if (!spmm_panel_wanted(probe0)) return gcn_feature_ld(d, dtype);
+  }
+  if (ld_line == ld) return ld;
   SpmmArgs probe{};
   probe.owner = const_cast<gcn_csr*>(A);
   probe.transposed = transposed;
@@ -87,9 +102,17 @@ using namespace gcn;
 extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W, const float* bias,
                              int d_in, int d_out, int act, int dtype, void* Z, void* Hout, void* AH_save,
                              void* stream) {
+  return gcn_layer_fwd_ld(A, H, ldh, W, bias, d_in, d_out, act, dtype, Z, d_out, Hout, d_out, AH_save, d_in, stream);
+}
+
+extern "C" int gcn_layer_fwd_ld(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W, const float* bias,
+                                int d_in, int d_out, int act, int dtype, void* Z, int64_t ldz, void* Hout, int64_t ldo,
+                                void* AH_save, int64_t ldah, void* stream) {
   clear_error();
   if (!A || !H || !W || !Hout) return fail(GCN_EINVAL, "gcn_layer_fwd: NULL argument");
   if (d_in < 1 || d_out < 1 || ldh < d_in) return fail(GCN_EINVAL, "gcn_layer_fwd: bad dimensions");
+  if (ldo < d_out || (Z && ldz < d_out) || (AH_save && ldah < d_in))
+    return fail(GCN_EINVAL, "gcn_layer_fwd: leading dimension smaller than the row");
   if (act != GCN_ACT_NONE && act != GCN_ACT_RELU) return fail(GCN_EINVAL, "gcn_layer_fwd: unknown activation");
   if (dtype != GCN_F32 && dtype != GCN_BF16) return fail(GCN_EINVAL, "gcn_layer_fwd: unknown dtype");
   gcn_csr* Am = const_cast<gcn_csr*>(A);
@@ -105,18 +128,19 @@ extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
     void* hub = ws.take(spmm_ws_bytes(&A->sched, sparse_first ? d_in : d_out));
     if (sparse_first) {
       void* AH = AH_save ? AH_save : ws.take((size_t)A->nr * d_in * es);
+      const int64_t ldAH = AH_save ? ldah : (int64_t)d_in;
       const int64_t ldhp = padded_operand_ld(A, false, d_in, dtype, ldh);
       void* Hp = ldhp != ldh ? ws.take((size_t)A->nc * ldhp * es) : nullptr;
       if (pass) {
         if (Hp) GCN_TRY(pad_rows(H, ldh, Hp, ldhp, A->nc, d_in, dtype, s));
-        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, Hp ? Hp : H, Hp ? ldhp : ldh, AH, d_in,
+        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, Hp ? Hp : H, Hp ? ldhp : ldh, AH, ldAH,
                     nullptr, 0, d_in, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
         sp.owner = Am;
         sp.x_rows_padded = Hp != nullptr;
         GCN_TRY(spmm_launch(sp, hub, s));
         GemmEpilogue epi;
-        epi.bias = bias; epi.relu = relu; epi.C2 = Z; epi.ldc2 = d_out;
-        GCN_TRY(gemm_nn(AH, d_in, W, d_out, Hout, d_out, A->nr, d_out, d_in, dtype, epi, s));
+        epi.bias = bias; epi.relu = relu; epi.C2 = Z; epi.ldc2 = ldz;
+        GCN_TRY(gemm_nn(AH, ldAH, W, d_out, Hout, ldo, A->nr, d_out, d_in, dtype, epi, s));
       }
     } else {
       const int64_t ldp = gather_ld_for(A, false, d_out, dtype);
@@ -124,7 +148,7 @@ extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
       if (pass) {
         GemmEpilogue epi;
         GCN_TRY(gemm_nn(H, ldh, W, d_out, P, ldp, A->nc, d_out, d_in, dtype, epi, s));
-        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, P, ldp, Hout, d_out, Z, d_out,
+        SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, P, ldp, Hout, ldo, Z, ldz,
                     d_out, dtype, relu ? GCN_EPI_RELU : GCN_EPI_NONE, bias, nullptr, 0};
         sp.owner = Am;
         sp.x_rows_padded = true;
@@ -139,9 +163,18 @@ extern "C" int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
 extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, const void* AH_saved, const float* W,
                              int d_in, int d_out, int dtype, const void* G, const void* Zprev, float* dW,
                              float* dbias, void* dH, void* stream) {
+  return gcn_layer_bwd_ld(A, H, ldh, AH_saved, d_in, W, d_in, d_out, dtype, G, d_out, Zprev, d_in, dW, dbias, dH, d_in, stream);
+}
+
+extern "C" int gcn_layer_bwd_ld(const gcn_csr_t* A, const void* H, int64_t ldh, const void* AH_saved, int64_t ldah,
+                                const float* W, int d_in, int d_out, int dtype, const void* G, int64_t ldg,
+                                const void* Zprev, int64_t ldzp, float* dW, float* dbias, void* dH, int64_t lddh,
+                                void* stream) {
   clear_error();
   if (!A || !H || !W || !G || !dW) return fail(GCN_EINVAL, "gcn_layer_bwd: NULL argument");
   if (d_in < 1 || d_out < 1 || ldh < d_in) return fail(GCN_EINVAL, "gcn_layer_bwd: bad dimensions");
+  if (ldg < d_out || (AH_saved && ldah < d_in) || (Zprev && ldzp < d_in) || (dH && lddh < d_in))
+    return fail(GCN_EINVAL, "gcn_layer_bwd: leading dimension smaller than the row");
   if (dtype != GCN_F32 && dtype != GCN_BF16) return fail(GCN_EINVAL, "gcn_layer_bwd: unknown dtype");
   if (dH && !A->colptr) return fail(GCN_EINVAL, "gcn_layer_bwd: dH needs a handle built with GCN_BUILD_CSC");
   gcn_csr* Am = const_cast<gcn_csr*>(A);
@@ -159,7 +192,7 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
     void* hub = ws.take(hub_bytes);
     float* Wt = (float*)ws.take(sizeof(float) * (size_t)d_in * d_out);
     void* cs = dbias ? ws.take(colsum_ws_bytes(A->nr, d_out)) : nullptr;
-    if (pass && dbias) GCN_TRY(colsum(G, d_out, A->nr, d_out, dtype, dbias, cs, s));
+    if (pass && dbias) GCN_TRY(colsum(G, ldg, A->nr, d_out, dtype, dbias, cs, s));
 
     if (via_T) {
       const int64_t ldt = round_up(d_out, 4);
@@ -168,13 +201,16 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
       void* tn = ws.take(gemm_tn_ws_bytes(kd, d_in, d_out));
       // rows of G whose pitch is not a multiple of 16 bytes are first copied to a padded buffer: the
       // sparse product then gathers with vector loads
-      const int64_t ldg = gather_ld_for(A, true, d_out, dtype);
-      const bool pad_g = ldg != d_out;
-      void* Gp = pad_g ? ws.take((size_t)A->nr * ldg * es) : nullptr;
+      // a caller's G that the sparse product cannot gather with 16-byte requests, or only across more lines than
+      // need be, is first copied to a padded buffer
+      const int64_t ldgp = (ldg * (int64_t)es) % 16 != 0 || ((uintptr_t)G % 16) != 0 || (d_out * (int64_t)es) % 16 != 0
+                               ? gather_ld_for(A, true, d_out, dtype) : padded_operand_ld(A, true, d_out, dtype, ldg);
+      const bool pad_g = ldgp != ldg;
+      void* Gp = pad_g ? ws.take((size_t)A->nr * ldgp * es) : nullptr;
       if (pass) {
-        if (pad_g) GCN_TRY(pad_rows(G, d_out, Gp, ldg, A->nr, d_out, dtype, s));
+        if (pad_g) GCN_TRY(pad_rows(G, ldg, Gp, ldgp, A->nr, d_out, dtype, s));
         SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, pad_g ? Gp : G,
-                    pad_g ? ldg : (int64_t)d_out, T, ldt, nullptr, 0, d_out, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
+                    pad_g ? ldgp : ldg, T, ldt, nullptr, 0, d_out, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
         sp.x_rows_padded = pad_g;
         sp.owner = Am;
         GCN_TRY(spmm_launch(sp, hub, s));
@@ -182,13 +218,13 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
           GCN_TRY(transpose_f32(W, d_in, d_out, Wt, s));
           // owned rows carry the ReLU mask, halo rows do not: two calls, so that each is uniform in its epilogue
           GemmEpilogue epi;
-          epi.mask = Zprev; epi.ldmask = d_in; epi.mask_rows = Zprev ? A->nr : 0;
-          GCN_TRY(gemm_nn(T, ldt, Wt, d_in, dH, d_in, A->nr, d_in, d_out, dtype, epi, s));
+          epi.mask = Zprev; epi.ldmask = ldzp; epi.mask_rows = Zprev ? A->nr : 0;
+          GCN_TRY(gemm_nn(T, ldt, Wt, d_in, dH, lddh, A->nr, d_in, d_out, dtype, epi, s));
           if (A->nh > 0)
-            GCN_TRY(gemm_nn((const char*)T + (size_t)A->nr * ldt * es, ldt, Wt, d_in, (char*)dH + (size_t)A->nr * d_in * es, d_in,
+            GCN_TRY(gemm_nn((const char*)T + (size_t)A->nr * ldt * es, ldt, Wt, d_in, (char*)dH + (size_t)A->nr * lddh * es, lddh,
                             A->nh, d_in, d_out, dtype, GemmEpilogue(), s));
         }
-        if (AH_saved) GCN_TRY(gemm_tn(AH_saved, d_in, G, d_out, dW, d_out, A->nr, d_in, d_out, dtype, tn, s));
+        if (AH_saved) GCN_TRY(gemm_tn(AH_saved, ldah, G, ldg, dW, d_out, A->nr, d_in, d_out, dtype, tn, s));
         else GCN_TRY(gemm_tn(H, ldh, T, ldt, dW, d_out, A->nc, d_in, d_out, dtype, tn, s));
       }
     } else {
@@ -203,14 +239,14 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
         if (dH) {
           GCN_TRY(transpose_f32(W, d_in, d_out, Wt, s));
           GemmEpilogue epi;
-          GCN_TRY(gemm_nn(G, d_out, Wt, d_in, Q, ldq, A->nr, d_in, d_out, dtype, epi, s));
-          SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, Q, ldq, dH, d_in, nullptr, 0,
-                      d_in, dtype, Zprev ? GCN_EPI_MASK : GCN_EPI_NONE, nullptr, Zprev, d_in};
+          GCN_TRY(gemm_nn(G, ldg, Wt, d_in, Q, ldq, A->nr, d_in, d_out, dtype, epi, s));
+          SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, Q, ldq, dH, lddh, nullptr, 0,
+                      d_in, dtype, Zprev ? GCN_EPI_MASK : GCN_EPI_NONE, nullptr, Zprev, ldzp};
           sp.owner = Am;
           sp.x_rows_padded = true;
           GCN_TRY(spmm_launch(sp, hub, s));
         }
-        const void* ah = AH_saved; int64_t ldah = d_in;
+        const void* ah = AH_saved; int64_t ld_ah = ldah;
         if (!AH_saved) {
           if (Hp) GCN_TRY(pad_rows(H, ldh, Hp, ldhp, A->nc, d_in, dtype, s));
           SpmmArgs sp{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, Hp ? Hp : H, Hp ? ldhp : ldh, AH, ldq,
@@ -218,9 +254,9 @@ extern "C" int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, con
           sp.owner = Am;
           sp.x_rows_padded = Hp != nullptr;
           GCN_TRY(spmm_launch(sp, hub, s));
-          ah = AH; ldah = ldq;
+          ah = AH; ld_ah = ldq;
         }
-        GCN_TRY(gemm_tn(ah, ldah, G, d_out, dW, d_out, A->nr, d_in, d_out, dtype, tn, s));
+        GCN_TRY(gemm_tn(ah, ld_ah, G, ldg, dW, d_out, A->nr, d_in, d_out, dtype, tn, s));
       }
     }
     if (!pass) GCN_TRY(ensure_workspace(Am, ws.used));

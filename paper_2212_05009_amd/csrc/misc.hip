@@ -2,6 +2,7 @@
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
+#include <string.h>
 
 #include <atomic>
 
@@ -111,11 +112,7 @@ static int gather_v(const char* table, int64_t ldb, int64_t nt, int n_vec, const
   const double by = 2.0 * (double)n_idx * n_vec * VB + 4.0 * (double)n_idx;
   ProfScope ps(GCN_K_GATHER, s, d, dtype, n_idx, 0, by, by, 0.0);
   if (is_host_memory(table)) {
-    static const int host_blocks = [] {
-      const char* e = getenv("GCN_GATHER_HOST_BLOCKS");
-      const int v = e ? atoi(e) : 0;
-      return v >= 1 && v <= 4096 ? v : 32;
-    }();
+    const int host_blocks = tune().gather_host_blocks;
     const unsigned nb = (unsigned)std::min<int64_t>(host_blocks, ceil_div(n_idx, 8));
     if (n_vec <= 4) k_gather_host<VB, 4><<<nb, 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
     else if (n_vec <= 8) k_gather_host<VB, 8><<<nb, 256, 0, s>>>(table, ldb, nt, n_vec, idx, n_idx, recv, ldrb);
@@ -456,6 +453,56 @@ __global__ __launch_bounds__(256) void k_sgd(float* __restrict__ W, const float*
 using namespace gcn;
 
 extern "C" const char* gcn_last_error(void) { return g_err; }
+
+namespace gcn {
+namespace {
+struct TuneField { const char* name; int Tuning::*field; int lo, hi; };
+const TuneField kTuneFields[] = {
+    {"GCN_SPMM_PANEL", &Tuning::spmm_panel, -1, 1},         {"GCN_PANEL_NARROW", &Tuning::panel_narrow, 0, 1},
+    {"GCN_PANEL_NOSYNC", &Tuning::panel_nosync, 0, 1},      {"GCN_PANEL_VERBOSE", &Tuning::panel_verbose, 0, 1},
+    {"GCN_SPMM_SLICES", &Tuning::spmm_slices, 0, 8},        {"GCN_SPMM_EPG", &Tuning::spmm_epg, 0, 1 << 20},
+    {"GCN_SPMM_WIDE", &Tuning::spmm_wide, 0, 1},            {"GCN_GEMM_DIRECT", &Tuning::gemm_direct, 0, 1},
+    {"GCN_GEMM_FAST", &Tuning::gemm_fast, 0, 1},            {"GCN_GEMM_TN_WIDE", &Tuning::gemm_tn_wide, 0, 1},
+    {"GCN_GEMM_BF16", &Tuning::gemm_bf16, 0, 1},            {"GCN_GEMM_TN_BLOCKS", &Tuning::gemm_tn_blocks, 1, 1 << 16},
+    {"GCN_GATHER_HOST_BLOCKS", &Tuning::gather_host_blocks, 1, 4096},
+};
+Tuning& tuning_storage() {
+  static Tuning t = [] {
+    Tuning v;
+    for (const TuneField& f : kTuneFields) {
+      const char* e = getenv(f.name);
+      if (!e || !*e) continue;
+      const long x = strtol(e, nullptr, 10);
+      if (x >= f.lo && x <= f.hi) v.*(f.field) = (int)x;
+    }
+    return v;
+  }();
+  return t;
+}
+}  // namespace
+const Tuning& tune() { return tuning_storage(); }
+}  // namespace gcn
+
+extern "C" int gcn_debug_set_tuning(const char* name, int value) {
+  clear_error();
+  if (!name) return fail(GCN_EINVAL, "gcn_debug_set_tuning: NULL name");
+  for (const TuneField& f : kTuneFields) {
+    if (strcmp(name, f.name) != 0) continue;
+    if (value == GCN_TUNE_DEFAULT) { tuning_storage().*(f.field) = Tuning().*(f.field); return GCN_OK; }
+    if (value < f.lo || value > f.hi) return fail(GCN_EINVAL, "gcn_debug_set_tuning: %s takes %d .. %d", f.name, f.lo, f.hi);
+    tuning_storage().*(f.field) = value;
+    return GCN_OK;
+  }
+  return fail(GCN_EINVAL, "gcn_debug_set_tuning: unknown name %s", name);
+}
+
+extern "C" int64_t gcn_feature_ld(int d, int dtype) {
+  if (d < 1 || (dtype != GCN_F32 && dtype != GCN_BF16)) return -1;
+  const int64_t es = dtype == GCN_BF16 ? 2 : 4;
+  const int64_t lines = ceil_div((int64_t)d * es, 128);
+  if (lines < 2) return d;
+  return (lines | 1) * (128 / es);
+}
 
 extern "C" int gcn_debug_max_grid_x(int64_t blocks) {
   clear_error();

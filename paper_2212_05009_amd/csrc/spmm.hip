@@ -25,23 +25,40 @@ size_t spmm_ws_bytes(const Schedule* sc, int d) {
 
 static bool aligned(const void* p, size_t a) { return p == nullptr || ((uintptr_t)p % a) == 0; }
 
-// Number of feature slices.  Blocks are handed to the 8 XCDs round-robin, so with S slices and
-// slice = block % S every XCD only ever touches 1/S of each feature row and its 4 MB L2 holds S times
-// as many distinct rows; the price is that the sparse arrays are streamed S times and that a lane
-// group gets narrower.  A slice never goes below 128 bytes, the L2 line: two XCDs that each want
-// half a line both fetch all of it.  Measured on a 134 MB feature matrix (2^18 x 128 fp32, R-MAT):
-// L2 misses 3.2 GB (S=1), 2.7 GB (S=2), 2.2 GB (S=4); time 533 / 463 / 475 us.
-static int pick_slices(const SpmmArgs& a, size_t es) {
-  const char* env = getenv("GCN_SPMM_SLICES");      // override for experiments
-  const int forced = env ? atoi(env) : 0;
-  const double xbytes = (double)a.n_cols * a.d * (double)es;
+// Feature slices.  Blocks are handed to the 8 XCDs round-robin, so with S slices and slice = block % S every XCD
+// only ever touches 1/S of each feature row and its 4 MB L2 holds S times as many distinct rows; the price is that
+// the sparse arrays are streamed S times and that a lane group gets narrower.
+//
+// Slices are whole 128-byte lines (two XCDs that each want half a line both fetch all of it), so slicing needs rows
+// that start on a line: pitch a multiple of 128 bytes, base aligned.  What decides how far to go is the pitch counted
+// in lines, P: slice s of row j is line j * P + s, and an XCD that only asks for lines = s (mod P) uses the few L2
+// channels (and memory channels) those addresses select when P is a power of two.  Measured on a 2.45 M x 256 fp32
+// operand (R-MAT, 126 M entries): pitch 8 lines 17.6 / 15.4 / 15.5 / 17.2 ms for S = 1 / 2 / 4 / 8, pitch 9 lines
+// 16.5 / 14.7 / 13.9 ms for S = 2 / 4 / 8 (L2 hits 19 % -> 33 %).  With an odd pitch every slice gets one line
+// (up to 8 slices); otherwise the earlier rule stands: two slices for operands above 100 MB whose halves are whole lines.
+// Returns S and sets *vps (vectors of V elements per slice; 0: split evenly).
+static int pick_slices(const SpmmArgs& a, size_t es, int V, int* vps) {
+  *vps = 0;
+  const int forced = tune().spmm_slices;                 // override for experiments
+  const int64_t row_bytes = (int64_t)a.d * (int64_t)es, pitch = a.ldx * (int64_t)es;
+  const double xbytes = (double)a.n_cols * (double)row_bytes;
+  const bool on_lines = pitch % 128 == 0 && aligned(a.X, 128) && (int64_t)V * (int64_t)es == 16;
+  const int64_t nl = ceil_div(row_bytes, 128);
+  if (on_lines && nl >= 2 && ((pitch / 128) & 1) && (forced > 0 || xbytes > 16e6)) {
+    int S = 2;
+    while (S < nl && S < 8) S <<= 1;
+    if (forced > 0 && forced < S) S = forced;
+    if (S != 1 && S != 2 && S != 4 && S != 8) S = 1;
+    *vps = (int)(ceil_div(nl, S) * 8);                   // 8 vectors of 16 bytes per line
+    return S;
+  }
   int S = 1;
   if (forced > 0) S = forced;
   else if (xbytes > 100e6) S = 2;
-  while (S > 1 && (double)a.d * (double)es / S < 128.0) S >>= 1;
+  while (S > 1 && (double)row_bytes / S < 128.0) S >>= 1;
   // a slice that does not consist of whole 128-byte lines makes every gathered row touch more lines in all than
   // the undivided row does: 400-byte rows (width 100) in two slices took 11.7 ms where one slice takes 8.0 ms
-  if (forced <= 0 && S > 1 && ((int64_t)a.d * (int64_t)es) % (128 * S) != 0) S = 1;
+  if (forced <= 0 && S > 1 && row_bytes % (128 * S) != 0) S = 1;
   if (S != 1 && S != 2 && S != 4 && S != 8) S = 1;
   return S;
 }
@@ -67,7 +84,7 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
   int V = a.dtype == GCN_BF16 ? 8 : 4;
   while (V > 1 && !((a.ldx % V) == 0 && aligned(a.X, V * es) && ((a.d % V) == 0 || a.x_rows_padded))) V >>= 1;
   k.y_vec = (a.ldy % V) == 0 && aligned(a.Y, V * es) && (!a.Y2 || ((a.ldy2 % V) == 0 && aligned(a.Y2, V * es)));
-  k.S = pick_slices(a, es);
+  k.S = pick_slices(a, es, V, &k.vps);
   SpmmProf pf;
   pf.kind = a.transposed ? GCN_K_SPMM_T : GCN_K_SPMM; pf.dtype = a.dtype; pf.rows = a.n_rows; pf.nnz = a.nnz;
   const double csr = 8.0 * (double)a.nnz + 8.0 * (double)(a.n_rows + 1), fe = (double)es * a.d;
@@ -77,7 +94,7 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
   // 32-bit addressing of X: row index and row pitch below 2^24, whole matrix below 4 GiB
   const double xspan = (double)a.n_cols * (double)a.ldx * (double)es;
   const bool narrow = a.n_cols < (1 << 24) && (double)a.ldx * (double)es < (double)(1 << 24) && xspan < 4294967296.0 &&
-                      !getenv("GCN_SPMM_WIDE");
+                      !tune().spmm_wide;
   k.row_bytes = narrow ? (uint32_t)(a.ldx * (int64_t)es) : 0u;
   if (a.dtype == GCN_BF16) return spmm_dispatch_bf16(k, a.sched, pf, V, narrow, s);
   return spmm_dispatch_f32(k, a.sched, pf, V, narrow, s);

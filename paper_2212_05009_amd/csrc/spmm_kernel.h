@@ -93,8 +93,8 @@ __device__ __forceinline__ float lane_read(int byte_addr, float v) {
 // gg, gg + groups, ... of the batch, fetching index and value from the owning lane by a cross-lane
 // read, and keeps U gathered feature vectors in flight.  When every team of the wavefront holds a
 // full batch no entry needs a validity check (the common case for long rows); otherwise loads are
-// predicated.  Lanes without a feature vector in this slice (active == false) gather vector 0 of the
-// same row - a valid address - and never store.  Different teams of a wavefront may hold rows of
+// predicated.  Lanes without a feature vector in this slice (active == false) are handed the slice's
+// first vector by the caller (c0) - a valid address in a line the slice reads anyway - and never store.  Different teams of a wavefront may hold rows of
 // different length: every cross-lane operation sits outside divergent code and loop exits are
 // taken on wave-wide votes.  LGR >= 0 fixes lgr at compile time.
 template <typename T, int V, int LPR, int U, bool NARROW, int LGR>
@@ -104,7 +104,8 @@ __device__ __forceinline__ void team_accumulate(const SpmmK& a, int64_t s, int64
   const int lgr = LGR >= 0 ? LGR : lgr_rt;
   const int groups = 1 << lgr;
   const int TL = LPR << lgr;
-  const uint32_t c0b = active ? (uint32_t)(c0 * (int64_t)sizeof(T)) : 0u;
+  const uint32_t c0b = (uint32_t)(c0 * (int64_t)sizeof(T));
+  (void)active;
   const int src0 = (team_lane0 + gg) << 2;          // byte address of the lane holding entry gg
   int64_t base = s;
   int32_t jreg = 0; float wreg = 0.f;
@@ -245,7 +246,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     for (int t0 = v_lo; t0 < v_hi; t0 += LPR) {
       const int vi = t0 + l;
       const bool active = vi < v_hi;
-      const int64_t c0 = (int64_t)vi * V;
+      const int64_t c0 = (int64_t)(active ? vi : v_lo) * V;
       float acc[V];
 #pragma unroll
       for (int v = 0; v < V; ++v) acc[v] = 0.f;
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
   for (int t0 = v_lo; t0 < v_hi; t0 += LPR) {
     const int vi = t0 + l;
     const bool active = vi < v_hi;
-    const int64_t c0 = (int64_t)vi * V;
+    const int64_t c0 = (int64_t)(active ? vi : v_lo) * V;
     float acc[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) acc[v] = 0.f;
@@ -345,8 +346,7 @@ static int launch_l(SpmmK& k, const Schedule* sc, const SpmmProf& pf, bool narro
     const int64_t cnt = sc->class_begin[c + 1] - sc->class_begin[c];
     if (cnt <= 0) continue;
     const int64_t len_hi = c >= 32 ? 0 : ((int64_t)1 << (32 - c)) - 1;
-    static const int epg_env = [] { const char* e = getenv("GCN_SPMM_EPG"); return e ? atoi(e) : 0; }();
-    const int epg = epg_env > 0 ? epg_env : kEntriesPerGroup;
+    const int epg = tune().spmm_epg > 0 ? tune().spmm_epg : kEntriesPerGroup;
     const int64_t want = ceil_div(len_hi > 0 ? len_hi : 1, epg);
     int groups = pow2_ceil_i((int)(want < G ? want : G));
     if (groups > G) groups = G;
@@ -382,7 +382,7 @@ static int launch_l(SpmmK& k, const Schedule* sc, const SpmmProf& pf, bool narro
 template <typename T, int V>
 static int launch_v(SpmmK& k, const Schedule* sc, const SpmmProf& pf, bool narrow, hipStream_t s) {
   k.nvec = (int)ceil_div(k.d, V);
-  k.vps = (int)ceil_div(k.nvec, k.S);
+  if (k.vps <= 0) k.vps = (int)ceil_div(k.nvec, k.S);     // else: whole lines per slice, set by the caller
   if (k.vps <= 4) return launch_l<T, V, 4>(k, sc, pf, narrow, s);
   if (k.vps <= 8) return launch_l<T, V, 8>(k, sc, pf, narrow, s);
   if (k.vps <= 16) return launch_l<T, V, 16>(k, sc, pf, narrow, s);

@@ -701,7 +701,7 @@ int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shif
   k_plan_scatter<<<grid, 256, 0, s>>>(sorted, spay, d_idx, d_val, nnz, kLidBits + cbbits, groups, epb, oseg.as<int64_t>(), P->wb, P->ent);
   GCN_CHECK_LAUNCH();
   GCN_HIP(hipStreamSynchronize(s));      // host vectors and temporaries go out of scope
-  if (getenv("GCN_PANEL_VERBOSE"))
+  if (tune().panel_verbose)
     fprintf(stderr, "[panel plan] rows %lld nnz %lld ns %d sw %d lpg %d cb_shift %d part_len %d vrows %lld panels %d nv_max %d batches %lld (padding %.1f%%)\n",
             (long long)n, (long long)nnz, ns, sw, lpg, cb_shift, part_len, (long long)total_v, n_panels, nv_max,
             (long long)n_batches, 100.0 * ((double)n_ent / (double)nnz - 1.0));
@@ -720,8 +720,7 @@ void free_panel_plans(gcn_csr* A) {
 // Whether the column sweep serves this product, and in which shape: lane-group width sw (features), lanes per
 // group, feature slices ns, and the column-block size 2^cb_shift.
 static bool panel_shape(const SpmmArgs& a, int* sw_out, int* lpg_out, int* ns_out, int* cb_shift_out) {
-  const char* env = getenv("GCN_SPMM_PANEL");            // 0: never, 1: whenever the limits allow
-  const int force = env ? atoi(env) : -1;
+  const int force = tune().spmm_panel;                   // 0: never, 1: whenever the limits allow
   if (force == 0 || !a.owner || a.n_rows < 1 || a.nnz < 1 || a.part != 0) return false;
   const size_t es = a.dtype == GCN_BF16 ? 2 : 4;
   // limits of the packed entry format and of 32-bit addressing of X
@@ -734,7 +733,7 @@ static bool panel_shape(const SpmmArgs& a, int* sw_out, int* lpg_out, int* ns_ou
   if (!((a.ldx % V) == 0 && aligned(a.X, 16) && ((a.d % V) == 0 || a.x_rows_padded))) return false;
   // lane-group shape: half a wavefront per row (128 fp32 features) for wide fp32 products, else 32
   // features per group (16 for products no wider than that)
-  const bool wide = a.dtype == GCN_F32 && a.d >= 64 && !getenv("GCN_PANEL_NARROW");
+  const bool wide = a.dtype == GCN_F32 && a.d >= 64 && !tune().panel_narrow;
   const int sw = wide ? 128 : a.d <= 16 ? 16 : 32;
   const int ns = (int)ceil_div(a.d, sw);
   // bytes of L2 one row of the operand occupies in an XCD that works on one slice
@@ -790,7 +789,7 @@ int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used) {
   k.ent = P->ent; k.wb = P->wb; k.nfull = P->nfull; k.cbend = P->cbend; k.obase = P->obase;
   k.panel_row0 = P->panel_row0; k.row_v = P->row_v; k.vlds = P->vlds; k.order = P->order;
   k.ctr = P->ctr; k.n_panels = P->n_panels; k.ns = ns; k.n_cb = P->n_cb;
-  k.soft_sync = getenv("GCN_PANEL_NOSYNC") ? 0 : 1;      // experiment switch
+  k.soft_sync = tune().panel_nosync ? 0 : 1;      // experiment switch
   k.wg_per_list = std::max(1, n_wg / kPanelLists);
   const int64_t units = (int64_t)ns * P->n_panels;
   if (kPanelLists % ns == 0) {

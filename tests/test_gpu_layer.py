@@ -186,17 +186,20 @@ def test_layer_bwd_hubs_and_directed_block(gcn, dev, hubs, directed_block):
 
 # ----------------------------------------------------------------------------- softmax cross-entropy
 @pytest.mark.parametrize("d_in,d_out", [(128, 41), (41, 128), (256, 47), (200, 130), (130, 200)])
-def test_layer_with_the_column_sweep(gcn, dev, er, hubs, directed_block, d_in, d_out, monkeypatch):
+def test_layer_with_the_column_sweep(gcn, dev, er, hubs, directed_block, d_in, d_out):
     """The layer calls with the column-sweep form of the sparse product switched on: its operands inside the
     library then get rows that start on a 128-byte line (widths 41, 47, 130: pitches 64, 64, 160 elements)."""
-    monkeypatch.setenv("GCN_SPMM_PANEL", "1")
-    run_fwd(gcn, dev, er, d_in, d_out, bias=True, save_ah=True)
-    run_bwd(gcn, dev, er, d_in, d_out, dbias=True)
-    run_bwd(gcn, dev, er, d_in, d_out, saved_ah=True, mask=False)
-    run_fwd(gcn, dev, hubs, d_in, d_out)
-    run_bwd(gcn, dev, directed_block, d_in, d_out)
-    run_fwd(gcn, dev, er, d_in, d_out, bf16=True)
-    run_bwd(gcn, dev, er, d_in, d_out, bf16=True)
+    gcn.gcn_debug_set_tuning("GCN_SPMM_PANEL", 1)
+    try:
+        run_fwd(gcn, dev, er, d_in, d_out, bias=True, save_ah=True)
+        run_bwd(gcn, dev, er, d_in, d_out, dbias=True)
+        run_bwd(gcn, dev, er, d_in, d_out, saved_ah=True, mask=False)
+        run_fwd(gcn, dev, hubs, d_in, d_out)
+        run_bwd(gcn, dev, directed_block, d_in, d_out)
+        run_fwd(gcn, dev, er, d_in, d_out, bf16=True)
+        run_bwd(gcn, dev, er, d_in, d_out, bf16=True)
+    finally:
+        gcn.gcn_debug_set_tuning("GCN_SPMM_PANEL", None)
 
 
 @pytest.mark.parametrize("C", [1, 2, 3, 4, 5, 7, 8, 12, 16, 17, 32, 41, 47, 64, 65, 100, 130, 255, 256, 300])

@@ -1,6 +1,6 @@
 """GPU parity of the column-sweep (LDS panel) variant of gcn_spmm / gcn_spmm_t.
 
-The library picks this variant by itself only for large operands; GCN_SPMM_PANEL=1 makes it the
+The library picks this variant by itself only for large operands; gcn_debug_set_tuning("GCN_SPMM_PANEL", 1) makes it the
 path for every product its limits allow, so the small graphs here exercise it: ragged panels,
 rows cut into several virtual rows, all lane-group shapes (width <= 16, 32-wide slices, vector and
 scalar gathers, fp32 and bf16), every epilogue, and the transposed arrays of a directed block.
@@ -31,14 +31,10 @@ def dev():
 
 
 @pytest.fixture(autouse=True)
-def forced_sweep():
-    old = os.environ.get("GCN_SPMM_PANEL")
-    os.environ["GCN_SPMM_PANEL"] = "1"
+def forced_sweep(gcn):
+    gcn.gcn_debug_set_tuning("GCN_SPMM_PANEL", 1)
     yield
-    if old is None:
-        del os.environ["GCN_SPMM_PANEL"]
-    else:
-        os.environ["GCN_SPMM_PANEL"] = old
+    gcn.gcn_debug_set_tuning("GCN_SPMM_PANEL", None)
 
 
 @pytest.fixture(scope="module")
@@ -108,7 +104,7 @@ def test_sweep_is_run_to_run_identical_and_close_to_row_variant(gcn, dev, hubs):
     X = torch.randn(hubs.og.nc, 96, device=dev)
     Y1 = torch.empty(hubs.og.nr, 96, device=dev); Y2 = torch.empty_like(Y1); Y3 = torch.empty_like(Y1)
     gcn.gcn_spmm(hubs.A, X, Y1); gcn.gcn_spmm(hubs.A, X, Y2)
-    os.environ["GCN_SPMM_PANEL"] = "0"
+    gcn.gcn_debug_set_tuning("GCN_SPMM_PANEL", 0)
     gcn.gcn_spmm(hubs.A, X, Y3)
     torch.cuda.synchronize()
     assert torch.equal(Y1, Y2)
@@ -125,8 +121,8 @@ def test_sweep_is_picked_for_a_dense_neighbourhood_graph(gcn, dev, capfd):
     u = rng.integers(0, n, m); v = rng.integers(0, n, m)
     src = np.concatenate([u, v]).astype(np.int32); dst = np.concatenate([v, u]).astype(np.int32)
     case = Case(gcn, dev, src, dst, n)
-    del os.environ["GCN_SPMM_PANEL"]
-    os.environ["GCN_PANEL_VERBOSE"] = "1"
+    gcn.gcn_debug_set_tuning("GCN_SPMM_PANEL", None)
+    gcn.gcn_debug_set_tuning("GCN_PANEL_VERBOSE", 1)
     try:
         capfd.readouterr()
         run_spmm(gcn, dev, case, 64)
@@ -134,6 +130,6 @@ def test_sweep_is_picked_for_a_dense_neighbourhood_graph(gcn, dev, capfd):
         assert "[panel plan]" in err, "the heuristic did not choose the column-sweep variant"
         run_spmm(gcn, dev, case, 64, transpose=True, epilogue="mask")
     finally:
-        del os.environ["GCN_PANEL_VERBOSE"]
-        os.environ["GCN_SPMM_PANEL"] = "1"
+        gcn.gcn_debug_set_tuning("GCN_PANEL_VERBOSE", None)
+        gcn.gcn_debug_set_tuning("GCN_SPMM_PANEL", 1)
         case.A.free()

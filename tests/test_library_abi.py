@@ -58,6 +58,20 @@ def test_argument_validation_without_gpu(lib):
     assert lib.gcn_softmax_xent(None, i64(1), i64(0), 0, 0, None, ctypes.c_float(1.0), None, None, i64(1), None) == -1
 
 
+def test_tuning_setter_and_feature_pitch_without_gpu(lib):
+    lib.gcn_last_error.restype = ctypes.c_char_p
+    lib.gcn_feature_ld.restype = ctypes.c_int64
+    assert lib.gcn_debug_set_tuning(b"GCN_NO_SUCH_RULE", 1) == -1 and b"unknown name" in lib.gcn_last_error()
+    assert lib.gcn_debug_set_tuning(b"GCN_SPMM_SLICES", 9) == -1
+    assert lib.gcn_debug_set_tuning(b"GCN_SPMM_SLICES", 4) == 0
+    assert lib.gcn_debug_set_tuning(b"GCN_SPMM_SLICES", -2147483648) == 0        # back to the default
+    assert lib.gcn_debug_set_tuning(None, 0) == -1
+    # rows start on a 128-byte line and the pitch is an odd number of lines; rows within one line keep their width
+    assert [lib.gcn_feature_ld(d, 0) for d in (16, 32, 47, 100, 128, 256, 602)] == [16, 32, 96, 160, 160, 288, 608]
+    assert [lib.gcn_feature_ld(d, 1) for d in (47, 64, 100, 256)] == [47, 64, 192, 320]
+    assert lib.gcn_feature_ld(0, 0) == -1 and lib.gcn_feature_ld(8, 7) == -1
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import torch
     import paper_2212_05009_amd as gcn
