@@ -146,6 +146,22 @@ def gemm(op: str, A, B):
     return Cm, Bd
 
 
+def gemm_dd(op: str, A, B):
+    """The same products for fp64 operands (no rounding of a factor that is itself an fp64 result)."""
+    A = np.ascontiguousarray(A, dtype=np.float64); B = np.ascontiguousarray(B, dtype=np.float64)
+    code = {"nn": 0, "nt": 1, "tn": 2}[op]
+    if code == 0:
+        M, K = A.shape; N = B.shape[1]; assert B.shape[0] == K
+    elif code == 1:
+        M, K = A.shape; N = B.shape[0]; assert B.shape[1] == K
+    else:
+        K, M = A.shape; N = B.shape[1]; assert B.shape[0] == K
+    Cm = np.empty((M, N), dtype=np.float64)
+    lib().orc_gemm_dd(C.c_int(code), C.c_int64(M), C.c_int64(N), C.c_int64(K), _p(A, C.c_double),
+                      C.c_int64(A.shape[1]), _p(B, C.c_double), C.c_int64(B.shape[1]), _p(Cm, C.c_double))
+    return Cm
+
+
 def layer_fwd(g: Graph, H, W, bias=None, act="relu"):
     """Returns dict(AH, Z, Hout, Bz), all fp64."""
     H, W = _f32(H), _f32(W)
@@ -192,12 +208,12 @@ def layer_bwd_pull(g: Graph, H_owned, W, G_all, Zprev=None):
     assert H_owned.shape == (g.nr, d_in) and G_all.shape == (g.nc, d_out)
     T, BT = spmm(g.rowptr, g.col, g.val, G_all)
     W64, H64 = W.astype(np.float64), H_owned.astype(np.float64)
-    S, BS = T @ W64.T, BT @ np.abs(W64).T
+    S, BS = gemm_dd("nt", T, W64), gemm_dd("nt", BT, np.abs(W64))
     if Zprev is not None:
         keep = _f32(Zprev) > 0
         assert keep.shape == S.shape
         S = np.where(keep, S, 0.0)
-    return {"T": T, "BT": BT, "dH": S, "BdH": BS, "dW": H64.T @ T, "BdW": np.abs(H64).T @ BT}
+    return {"T": T, "BT": BT, "dH": S, "BdH": BS, "dW": gemm_dd("tn", H64, T), "BdW": gemm_dd("tn", np.abs(H64), BT)}
 
 
 def softmax_xent(Z, y, scale):

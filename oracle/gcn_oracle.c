@@ -222,6 +222,23 @@ void orc_gemm(int op, int64_t M, int64_t N, int64_t K, const float* A, int64_t l
     }
 }
 
+/* The same three products for operands that are already fp64 (a product whose factor is itself
+ * an fp64 result, e.g. S = T W^T with T = A G in Sec. 4.2): C only, no bound. */
+void orc_gemm_dd(int op, int64_t M, int64_t N, int64_t K, const double* A, int64_t lda,
+                 const double* Bm, int64_t ldb, double* C) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < M; ++i)
+    for (int64_t j = 0; j < N; ++j) {
+      double s = 0.0;
+      for (int64_t k = 0; k < K; ++k) {
+        double a = (op == 2) ? A[k * lda + i] : A[i * lda + k];
+        double b = (op == 1) ? Bm[j * ldb + k] : Bm[k * ldb + j];
+        s += a * b;
+      }
+      C[i * N + j] = s;
+    }
+}
+
 /* ------------------------------------------------------------------------------------
  * Feedforward of one layer on a row block (Sec. 3.1 first equation; Sec. 4.1 per-row task
  * and block form):  Z(i,:) = ( sum_j A(i,j) H(j,:) ) W  (+ bias),  Hout = act(Z).

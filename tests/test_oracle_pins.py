@@ -251,6 +251,16 @@ def test_gemm_forms():
     # a non-square transposed case cannot be confused with the plain one
     C, _ = oracle.gemm("tn", A, rng.standard_normal((13, 4)).astype(np.float32))
     assert C.shape == (7, 4)
+    # the fp64-operand forms (used where a factor is itself an fp64 result): same three products, and one-hot
+    # selectors pick out columns / rows exactly, so a transposed operand or a swapped index cannot pass
+    A64b = rng.standard_normal((13, 7)); B64b = rng.standard_normal((7, 5))
+    np.testing.assert_allclose(oracle.gemm_dd("nn", A64b, B64b), A64b @ B64b, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(oracle.gemm_dd("nt", A64b, B64b.T.copy()), A64b @ B64b, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(oracle.gemm_dd("tn", A64b.T.copy(), B64b), A64b @ B64b, rtol=1e-13, atol=1e-14)
+    np.testing.assert_array_equal(oracle.gemm_dd("nn", A64b, sel.astype(np.float64)), A64b[:, [3, 6]])
+    np.testing.assert_array_equal(oracle.gemm_dd("nt", A64b, sel.T.astype(np.float64).copy()), A64b[:, [3, 6]])
+    rsel = np.zeros((13, 2)); rsel[2, 0] = 1; rsel[11, 1] = 1
+    np.testing.assert_array_equal(oracle.gemm_dd("tn", rsel, A64b), A64b[[2, 11], :])
 
 
 # ----------------------------------------------------------------------------- softmax cross-entropy
@@ -479,6 +489,68 @@ def test_one_layer_on_an_edgeless_graph_is_softmax_regression():
     want_W = (W.astype(np.float64) - 0.3 * (X.astype(np.float64).T @ G)).astype(np.float32)
     assert abs(losses[0] - want_loss) <= 1e-12 * abs(want_loss)
     assert np.array_equal(W1, want_W)
+
+
+def _dense_loss(Ad, X, Ws, y, scale):
+    """Independent fp64 model with any number of layers, dense numpy only (Sec. 3.1: H^k = relu(A^ H^(k-1) W^k) for
+    k < L, identity on layer L, softmax cross-entropy on Z^L)."""
+    H = X
+    for k, W in enumerate(Ws):
+        Z = Ad @ H @ W
+        H = Z if k == len(Ws) - 1 else np.maximum(Z, 0.0)
+    lse = np.log(np.exp(Z - Z.max(1, keepdims=True)).sum(1)) + Z.max(1)
+    return scale * (lse - Z[np.arange(len(y)), y]).sum()
+
+
+@pytest.mark.parametrize("dims,directed", [((6, 5, 4), False), ((6, 5, 4), True), ((5, 6, 4, 3), False)])
+def test_training_step_with_several_layers_is_gradient_descent_on_the_dense_model(dims, directed):
+    """oracle.train itself, for L = 2 and L = 3 (Sec. 3.1 last equation, W <- W - lr dJ/dW; Algorithm 2's update
+    line): after one epoch every weight must equal W - lr * (central difference of the dense fp64 loss), and the
+    loss it reports must be the dense model's.  A second epoch must be the same step taken from the new weights.
+    A dropped ReLU mask, a wrong gradient hand-over between layers or a transposed product changes dJ/dW."""
+    n, lr = 36, 0.4
+    src, dst = rand_edges(n, 150, 77, directed)
+    g = oracle.graph_build(src, dst, n)
+    Ad = csr_to_dense(g, g.val.astype(np.float64))
+    rng = np.random.default_rng(21)
+    X = rng.standard_normal((n, dims[0])).astype(np.float32)
+    Ws = [(0.6 * rng.standard_normal((dims[k], dims[k + 1]))).astype(np.float32) for k in range(len(dims) - 1)]
+    y = rng.integers(0, dims[-1], n).astype(np.int32)
+    scale = 1.0 / n
+    X64 = X.astype(np.float64)
+
+    def check_step(W_before, W_after, loss_reported):
+        W64 = [W.astype(np.float64) for W in W_before]
+        J0 = _dense_loss(Ad, X64, W64, y, scale)
+        assert abs(loss_reported - J0) <= 1e-6 * abs(J0)            # stored layer outputs are fp32
+        # no pre-activation may sit on a ReLU kink, or the central difference is not the derivative
+        H = X64
+        for W in W64[:-1]:
+            Z = Ad @ H @ W
+            assert np.abs(Z).min() > 1e-4
+            H = np.maximum(Z, 0.0)
+        h = 1e-6
+        for k, W in enumerate(W64):
+            for i in range(W.shape[0]):
+                for c in range(W.shape[1]):
+                    E = np.zeros_like(W); E[i, c] = h
+                    Wp = list(W64); Wm = list(W64)
+                    Wp[k] = W + E; Wm[k] = W - E
+                    fd = (_dense_loss(Ad, X64, Wp, y, scale) - _dense_loss(Ad, X64, Wm, y, scale)) / (2 * h)
+                    step = (float(W_before[k][i, c]) - float(W_after[k][i, c])) / lr
+                    # fp32 hand-overs between the layer calls, the fp32 rounding of the new weight, the difference quotient
+                    tol = 4e-6 * abs(fd) + 4e-8 + 1.2e-7 * abs(float(W_before[k][i, c])) / lr
+                    assert abs(step - fd) <= tol, (k, i, c, step, fd)
+
+    losses1, W1 = oracle.train(g, X, Ws, y, lr=lr, epochs=1)
+    assert any(np.any(a != b) for a, b in zip(Ws, W1))
+    check_step(Ws, W1, losses1[0])
+    losses2, W2 = oracle.train(g, X, Ws, y, lr=lr, epochs=2)
+    assert losses2[0] == losses1[0]
+    check_step(W1, W2, losses2[1])
+    # and it is bit for bit one more epoch from where the first stopped
+    _, W2b = oracle.train(g, X, W1, y, lr=lr, epochs=1)
+    assert all(np.array_equal(a, b) for a, b in zip(W2, W2b))
 
 
 def test_training_loss_falls_on_a_small_graph():
