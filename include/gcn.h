@@ -123,6 +123,22 @@ int gcn_spmm(const gcn_csr_t* A, const void* X, int64_t ldx, int d, int dtype, v
              void* stream);
 
 /*
+ * gcn_spmm for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and the same result as gcn_spmm's row kernel; the partial rows
+ * of long-row chunks go to a fixed 64 MiB device array of the library (held by every GPU the library runs on
+ * until the process ends) instead of the handle's workspace, the column-sweep variant (whose plan would have to
+ * be built) is never taken, and the launches are not recorded by the profiling hooks.  The call allocates and
+ * frees nothing and does not synchronise.
+ *   Limit: (chunks of 1024 entries of rows longer than 2048 entries) x d x 4 bytes <= 64 MiB; beyond it the
+ *   call returns GCN_EINVAL and enqueues nothing.
+ *   All calls on one GPU share that array: nothing in it has to start at zero (every partial row is written
+ *   before it is read), but two calls that overlap in time on one GPU (different streams) race on it.
+ */
+int gcn_spmm_noalloc(const gcn_csr_t* A, const void* X, int64_t ldx, int d, int dtype, void* Y,
+                     int64_t ldy, int epilogue, const float* bias, const void* Zprev, int64_t ldz,
+                     void* stream);
+
+/*
  * Y[nc x d] = epilogue( A^_m^T X[nr x d] )   (Sec. 3.1: for a directed graph backpropagation
  * uses the transpose).  Needs GCN_BUILD_CSC.  Rows nr..nc-1 of Y are the contributions of
  * this block to rows owned elsewhere.  GCN_EPI_MASK applies to the owned rows 0..nr-1 only

@@ -48,6 +48,8 @@ def _load():
     lib.gcn_csr_arrays.argtypes = [vp] + [C.POINTER(vp)] * 8
     lib.gcn_csr_free.argtypes = [vp]
     lib.gcn_spmm.argtypes = [vp, vp, C.c_int64, C.c_int, C.c_int, vp, C.c_int64, C.c_int, vp, vp, C.c_int64, vp]
+    lib.gcn_spmm_noalloc.argtypes = [vp, vp, C.c_int64, C.c_int, C.c_int, vp, C.c_int64, C.c_int, vp, vp, C.c_int64, vp]
+    lib.gcn_spmm_noalloc.restype = C.c_int
     lib.gcn_spmm_t.argtypes = [vp, vp, C.c_int64, C.c_int, C.c_int, vp, C.c_int64, C.c_int, vp, C.c_int64, vp]
     lib.gcn_halo_gather.argtypes = [vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, C.c_int64, vp, C.c_int64, vp]
     lib.gcn_layer_fwd.argtypes = [vp, vp, C.c_int64, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]
@@ -230,6 +232,24 @@ def gcn_spmm(A: Csr, X: torch.Tensor, Y: torch.Tensor, epilogue: int = EPI_NONE,
         raise TypeError("gcn_spmm: bias must be a contiguous f32 vector of length d")
     _check(_lib.gcn_spmm(A.handle, _ptr(X), ldx, d, _dtype_code(X), _ptr(Y), ldy, epilogue, _ptr(bias), _ptr(Zprev),
                          ldz, _stream()), "gcn_spmm")
+    return Y
+
+
+def gcn_spmm_noalloc(A: Csr, X: torch.Tensor, Y: torch.Tensor, epilogue: int = EPI_NONE, bias: torch.Tensor | None = None,
+                     Zprev: torch.Tensor | None = None):
+    """gcn_spmm through the entry point that allocates nothing (its scratch is a fixed array of the library)."""
+    ldx, d = _rowmajor(_dev(X), "X"); ldy, dy = _rowmajor(_dev(Y), "Y")
+    if X.shape[0] != A.nc or Y.shape[0] != A.nr or dy != d or Y.dtype != X.dtype:
+        raise TypeError("gcn_spmm_noalloc: X must be [nc, d] and Y [nr, d] of the same dtype")
+    ldz = 0
+    if Zprev is not None:
+        ldz, dz = _rowmajor(_dev(Zprev, X.dtype, "Zprev"), "Zprev")
+        if Zprev.shape[0] != A.nr or dz != d:
+            raise TypeError("gcn_spmm_noalloc: Zprev must be [nr, d]")
+    if bias is not None and (_dev(bias, torch.float32, "bias").numel() != d or not bias.is_contiguous()):
+        raise TypeError("gcn_spmm_noalloc: bias must be a contiguous f32 vector of length d")
+    _check(_lib.gcn_spmm_noalloc(A.handle, _ptr(X), ldx, d, _dtype_code(X), _ptr(Y), ldy, epilogue, _ptr(bias), _ptr(Zprev),
+                                 ldz, _stream()), "gcn_spmm_noalloc")
     return Y
 
 

@@ -61,6 +61,15 @@ struct ProfScope {
   hipStream_t s_;
 };
 
+// While one of these is alive on a host thread, ProfScope records nothing on that thread (recording creates
+// events on first use; the entry point that allocates nothing must not).
+struct ProfSuppress {
+  ProfSuppress();
+  ~ProfSuppress();
+  ProfSuppress(const ProfSuppress&) = delete;
+  ProfSuppress& operator=(const ProfSuppress&) = delete;
+};
+
 // RAII device buffer so that every error path frees what it allocated.
 struct DevBuf {
   void* p = nullptr;
@@ -242,6 +251,7 @@ struct SpmmArgs {
   int part = 0;
   const int64_t* mid = nullptr;
   gcn_csr* owner = nullptr;  // handle the arrays belong to (lets the launch cache a panel plan); may be null
+  bool no_alloc = false;     // the launch must not allocate: no column-sweep plan is built
 };
 // ws: workspace for hub partial sums, at least spmm_ws_bytes(sched, d)
 size_t spmm_ws_bytes(const Schedule* sc, int d);

@@ -20,12 +20,16 @@ std::atomic<int> g_only_d{-1};      // >= 0: only launches of this feature width
 std::mutex g_mu;
 std::vector<Slot> g_slots;      // events are created once and reused by later recordings
 int64_t g_used = 0, g_dropped = 0;
+thread_local int t_suppress = 0;
 }  // namespace
+
+ProfSuppress::ProfSuppress() { ++t_suppress; }
+ProfSuppress::~ProfSuppress() { --t_suppress; }
 
 ProfScope::ProfScope(int kind, hipStream_t s, int d, int dtype, int64_t rows, int64_t inner, double alg_bytes,
                      double touched_bytes, double flops)
     : s_(s) {
-  if (!g_enabled.load(std::memory_order_relaxed)) return;
+  if (!g_enabled.load(std::memory_order_relaxed) || t_suppress > 0) return;
   if (!((g_kind_mask.load(std::memory_order_relaxed) >> kind) & 1)) return;
   const int only_d = g_only_d.load(std::memory_order_relaxed);
   if (only_d >= 0 && d != only_d) return;

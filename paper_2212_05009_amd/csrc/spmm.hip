@@ -15,6 +15,8 @@
 // Every sum has a fixed association, so results are bitwise reproducible.
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "spmm_kernel.h"
 
 namespace gcn {
@@ -77,7 +79,7 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
   k.partial = (float*)ws; k.d = a.d; k.epilogue = a.epilogue;
   if (a.n_rows == 0) return GCN_OK;
   bool swept = false;
-  if (a.part == 0) GCN_TRY(spmm_panel_try(a, s, &swept));       // the column-sweep plan covers whole rows only
+  if (a.part == 0 && !a.no_alloc) GCN_TRY(spmm_panel_try(a, s, &swept));       // the column-sweep plan covers whole rows only
   if (swept) return GCN_OK;
   const size_t es = a.dtype == GCN_BF16 ? 2 : 4;
   // widest vector such that every feature-row load stays aligned (and inside the row's storage)
@@ -98,6 +100,29 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
   k.row_bytes = narrow ? (uint32_t)(a.ldx * (int64_t)es) : 0u;
   if (a.dtype == GCN_BF16) return spmm_dispatch_bf16(k, a.sched, pf, V, narrow, s);
   return spmm_dispatch_f32(k, a.sched, pf, V, narrow, s);
+}
+
+// ---- scratch of the entry point that allocates nothing ------------------------------------------------------
+// The partial rows of long-row chunks (n_chunks x d floats) of gcn_spmm_noalloc live in this fixed array instead
+// of the handle's workspace.  Every GPU the library runs on holds its own copy until the process ends.  The
+// array's name is a host-side stand-in: its device address is asked for once per device and kept.
+constexpr size_t kNoAllocScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_addr[kMaxDevices];
+
+static int noalloc_scratch(void** out) {
+  int dev = -1;
+  GCN_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(GCN_EINVAL, "gcn_spmm_noalloc: device ordinal %d is not supported", dev);
+  void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    GCN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));      // this device's copy (the current device)
+    if (!p) return fail(GCN_EHIP, "gcn_spmm_noalloc: no device address for the scratch array");
+    g_scratch_addr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return GCN_OK;
 }
 
 }  // namespace gcn
@@ -126,6 +151,26 @@ extern "C" int gcn_spmm(const gcn_csr_t* A, const void* X, int64_t ldx, int d, i
              d, dtype, epilogue, bias, Zprev, ldz};
   a.owner = Am;
   return spmm_launch(a, Am->ws, (hipStream_t)stream);
+}
+
+extern "C" int gcn_spmm_noalloc(const gcn_csr_t* A, const void* X, int64_t ldx, int d, int dtype, void* Y, int64_t ldy,
+                                int epilogue, const float* bias, const void* Zprev, int64_t ldz, void* stream) {
+  clear_error();
+  if (!A) return fail(GCN_EINVAL, "gcn_spmm_noalloc: NULL handle");
+  GCN_TRY(check_dense("gcn_spmm_noalloc", X, ldx, Y, ldy, d, dtype));
+  if (epilogue < GCN_EPI_NONE || epilogue > GCN_EPI_MASK) return fail(GCN_EINVAL, "gcn_spmm_noalloc: unknown epilogue");
+  if (epilogue == GCN_EPI_MASK && (!Zprev || ldz < d)) return fail(GCN_EINVAL, "gcn_spmm_noalloc: mask epilogue needs Zprev with ldz >= d");
+  const size_t need = spmm_ws_bytes(&A->sched, d);
+  if (need > kNoAllocScratchBytes)
+    return fail(GCN_EINVAL, "gcn_spmm_noalloc: %lld long-row chunks x %d features need %zu bytes of scratch, the fixed buffer holds %zu",
+                (long long)A->sched.n_chunks, d, need, kNoAllocScratchBytes);
+  void* ws = nullptr;
+  GCN_TRY(noalloc_scratch(&ws));
+  SpmmArgs a{A->rowptr, A->col, A->val, &A->sched, A->nr, A->nc, A->nnz, false, A->nr, X, ldx, Y, ldy, nullptr, 0,
+             d, dtype, epilogue, bias, Zprev, ldz};
+  a.no_alloc = true;
+  ProfSuppress quiet;
+  return spmm_launch(a, ws, (hipStream_t)stream);
 }
 
 extern "C" int gcn_spmm_t(const gcn_csr_t* A, const void* X, int64_t ldx, int d, int dtype, void* Y, int64_t ldy,
