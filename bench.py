@@ -403,6 +403,12 @@ def run_case(gcn, torch, name, dtype, steps, warmup, *, natural_ids=False, backw
            "kernels_from": f"a separate pass of {bsteps} epochs with every launch timed",
            "profile_records_dropped": dropped}
 
+    if calibrate_copy:
+        # the sparse products of one epoch in launch order: lets a counter run attribute its dispatches
+        per_epoch = len(recs) // bsteps
+        out["sparse_launch_order"] = [[r["kind"], r["d"]] for r in recs[:per_epoch] if r["kind"] in ("spmm", "spmm_t")]
+        out["sparse_sources"] = sparse_sources_digest()
+
     if block:
         # the host link's own rate: one plain copy of as many bytes as a halo fetch moves, from the same pinned
         # table, next to the rate of the gather kernel that reads the table through the index list

@@ -80,8 +80,10 @@ const char* gcn_last_error(void);
  *   n_global      number of vertices of the whole graph; every id must lie in [0, n_global).
  *   row_lo,row_hi owned rows; (0, n_global) means the whole graph.
  *   d_deg_global  device int32[n_global] or NULL: degrees INCLUDING the self-loop of every
- *                 global vertex.  Required when the block is not the whole graph (the degrees
- *                 of halo vertices cannot be derived from the block's own rows).
+ *                 global vertex, every entry >= 1.  Required when the block is not the whole graph:
+ *                 the degrees of halo vertices cannot be derived from the block's own rows.  Only
+ *                 those are read from it; an owned vertex's degree is always the entry count of its
+ *                 row, which the block holds whole (Sec. 4.1).
  *   flags         GCN_BUILD_CSC or 0.
  *
  * Result: CSR with columns in local numbering (owned j -> j - row_lo, halo -> nr + rank),
@@ -210,8 +212,9 @@ int gcn_layer_bwd_ld(const gcn_csr_t* A, const void* H, int64_t ldh, const void*
  *         "no label": no loss term, zero gradient row; y[i] >= C is treated the same way.
  *   loss  device f32 scalar (accumulated in fp64 in a fixed order: run-to-run identical).
  *   G     device [nr x C] (ldg), element type dtype.
- * The per-block partial sums live in a fixed device buffer of the library: two calls that
- * overlap in time on the same GPU race on it.
+ * The per-block partial sums live in a fixed device buffer of the library with 64 rows; every
+ * call takes the next row, so calls may overlap in time on different streams as long as fewer
+ * than 64 of them are in flight on one GPU.
  */
 int gcn_softmax_xent(const void* Z, int64_t ldz, int64_t nr, int C, int dtype, const int32_t* y,
                      float scale, float* loss, void* G, int64_t ldg, void* stream);

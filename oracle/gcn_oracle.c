@@ -124,13 +124,14 @@ int orc_graph_build(const int32_t* src, const int32_t* dst, int64_t n_edges, int
   for (int64_t i = 0; i < nr; ++i) g->rowptr[i + 1] += g->rowptr[i];
   free(key);
 
-  /* values: degree of local column c is that of its global vertex */
+  /* values.  D(i,i) is the row sum of A + I (Sec. 3.1).  A row block holds its rows whole (Sec. 4.1), so for an
+   * owned vertex that sum is the entry count of its row, counted above; only a halo vertex, whose row lives on
+   * another processor, takes its degree from deg_global. */
   for (int64_t i = 0; i < nr; ++i) {
-    int64_t di = deg_global ? deg_global[row_lo + i] : g->deg[i];
+    int64_t di = g->deg[i];
     for (int64_t k = g->rowptr[i]; k < g->rowptr[i + 1]; ++k) {
       int64_t c = g->col[k];
-      int64_t gid = c < nr ? row_lo + c : halo[c - nr];
-      int64_t dj = deg_global ? deg_global[gid] : g->deg[gid];
+      int64_t dj = c < nr ? g->deg[c] : deg_global[halo[c - nr]];
       float inv_i = 1.0f / sqrtf((float)di);
       float inv_j = 1.0f / sqrtf((float)dj);
       g->val[k] = inv_i * inv_j;

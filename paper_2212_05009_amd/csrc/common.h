@@ -162,6 +162,7 @@ struct Schedule {
 constexpr int kPanelWaves = 16;
 constexpr int kPanelLists = 8;      // one work list per XCD
 struct PanelPlan {
+  bool unusable = false;   // a record that the matrix does not fit the format for this shape (no arrays)
   bool transposed = false;
   int ns = 1;              // feature slices (32 wide) the panel size was chosen for
   int sw = 32;             // accumulator floats per virtual row: 32, or 16 for products of width <= 16

@@ -150,14 +150,11 @@ __global__ void k_values(const uint64_t* __restrict__ ukeys, int64_t nnz, int co
   uint64_t v = ukeys[p];
   int64_t i = (int64_t)(v >> colbits);
   int64_t c = (int64_t)(v & ((1ull << colbits) - 1ull));
-  int32_t di, dj;
-  if (deg_global) {
-    di = deg_global[row_lo + i];
-    dj = deg_global[c < nr ? row_lo + c : (int64_t)halo_gid[c - nr]];
-  } else {                                   // whole graph: local ids are global ids
-    di = deg_local[i];
-    dj = deg_local[c];
-  }
+  // an owned vertex's degree is the entry count of its row, which the block holds whole (Sec. 4.1); a halo
+  // vertex's row lives elsewhere: its degree comes from the caller's global array
+  (void)row_lo;
+  const int32_t di = deg_local[i];
+  const int32_t dj = c < nr ? deg_local[c] : deg_global[halo_gid[c - nr]];
   val[p] = __fmul_rn(inv_sqrt_deg(di), inv_sqrt_deg(dj));
 }
 

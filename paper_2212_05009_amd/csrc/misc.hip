@@ -137,12 +137,16 @@ static int gather_v(const char* table, int64_t ldb, int64_t nt, int n_vec, const
 // then per block in a fixed tree, then over the blocks in block order.
 // ------------------------------------------------------------------------------------------
 constexpr int kLossBlocks = 4096;
-__device__ double g_loss_partial[kLossBlocks];
+// Per-block partial sums of the loss.  Every call takes the next of kLossSlots rows (a host-side counter), so
+// calls that overlap in time on different streams do not share partials unless more than kLossSlots are in flight.
+constexpr int kLossSlots = 64;
+__device__ double g_loss_partial[kLossSlots][kLossBlocks];
+static std::atomic<unsigned> g_loss_slot{0};
 
 template <typename T, int LPR>
 __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, int64_t ldz, int64_t nr, int C,
                                                       const int32_t* __restrict__ y, float scale,
-                                                      T* __restrict__ G, int64_t ldg) {
+                                                      T* __restrict__ G, int64_t ldg, int slot) {
   constexpr int GR = 256 / LPR;
   const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
   double local = 0.0;
@@ -193,7 +197,7 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, i
     if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
     __syncthreads();
   }
-  if (threadIdx.x == 0) g_loss_partial[blockIdx.x] = red[0];
+  if (threadIdx.x == 0) g_loss_partial[slot][blockIdx.x] = red[0];
 }
 
 // The same for rows of 4 LPR >= C classes with 16-byte (fp32) / 8-byte (bf16) aligned rows and C a multiple of 4:
@@ -201,7 +205,7 @@ __global__ __launch_bounds__(256) void k_softmax_xent(const T* __restrict__ Z, i
 template <typename T, int LPR>
 __global__ __launch_bounds__(256) void k_softmax_xent_v4(const T* __restrict__ Z, int64_t ldz, int64_t nr, int C,
                                                          const int32_t* __restrict__ y, float scale,
-                                                         T* __restrict__ G, int64_t ldg) {
+                                                         T* __restrict__ G, int64_t ldg, int slot) {
   constexpr int GR = 256 / LPR;
   const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
   const bool in = 4 * l < C;
@@ -258,7 +262,7 @@ __global__ __launch_bounds__(256) void k_softmax_xent_v4(const T* __restrict__ Z
     if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
     __syncthreads();
   }
-  if (threadIdx.x == 0) g_loss_partial[blockIdx.x] = red[0];
+  if (threadIdx.x == 0) g_loss_partial[slot][blockIdx.x] = red[0];
 }
 
 // Rows of up to 4 LPR classes that the vector form above cannot take (C no multiple of 4, or rows not aligned): a lane
@@ -267,7 +271,7 @@ __global__ __launch_bounds__(256) void k_softmax_xent_v4(const T* __restrict__ Z
 template <typename T, int LPR>
 __global__ __launch_bounds__(256) void k_softmax_xent_s4(const T* __restrict__ Z, int64_t ldz, int64_t nr, int C,
                                                          const int32_t* __restrict__ y, float scale,
-                                                         T* __restrict__ G, int64_t ldg) {
+                                                         T* __restrict__ G, int64_t ldg, int slot) {
   constexpr int GR = 256 / LPR;
   const int g = threadIdx.x / LPR, l = threadIdx.x % LPR;
   double local = 0.0;
@@ -306,19 +310,20 @@ __global__ __launch_bounds__(256) void k_softmax_xent_s4(const T* __restrict__ Z
     if ((int)threadIdx.x < off) red[threadIdx.x] += red[threadIdx.x + off];
     __syncthreads();
   }
-  if (threadIdx.x == 0) g_loss_partial[blockIdx.x] = red[0];
+  if (threadIdx.x == 0) g_loss_partial[slot][blockIdx.x] = red[0];
 }
 
 // one block: thread t adds the partials t, t+256, ... in order, then a fixed tree over the threads
-__global__ __launch_bounds__(256) void k_loss_finish(int nblocks, float scale, float* __restrict__ loss) {
+__global__ __launch_bounds__(256) void k_loss_finish(int nblocks, float scale, float* __restrict__ loss, int slot) {
   __shared__ double red[256];
   double s = 0.0;
   int b = threadIdx.x;
   for (; b + 768 < nblocks; b += 1024) {           // four loads in flight, added in block order
-    const double v0 = g_loss_partial[b], v1 = g_loss_partial[b + 256], v2 = g_loss_partial[b + 512], v3 = g_loss_partial[b + 768];
+    const double* part = g_loss_partial[slot];
+    const double v0 = part[b], v1 = part[b + 256], v2 = part[b + 512], v3 = part[b + 768];
     s += v0; s += v1; s += v2; s += v3;
   }
-  for (; b < nblocks; b += 256) s += g_loss_partial[b];
+  for (; b < nblocks; b += 256) s += g_loss_partial[slot][b];
   red[threadIdx.x] = s;
   __syncthreads();
   for (int off = 128; off > 0; off >>= 1) {
@@ -331,6 +336,7 @@ __global__ __launch_bounds__(256) void k_loss_finish(int nblocks, float scale, f
 template <typename T>
 static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* y, float scale, float* loss, T* G,
                      int64_t ldg, hipStream_t s) {
+  const int slot = (int)(g_loss_slot.fetch_add(1u, std::memory_order_relaxed) % (unsigned)kLossSlots);
   const size_t vb = 4 * sizeof(T);
   if (C % 4 == 0 && C <= 256 && (ldz % 4) == 0 && (ldg % 4) == 0 && ((uintptr_t)Z % vb) == 0 && ((uintptr_t)G % vb) == 0) {
     int lpr4 = 1;
@@ -340,15 +346,15 @@ static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* 
     const double by4 = (double)nr * (2.0 * sizeof(T) * C + 4.0);
     ProfScope ps(GCN_K_SOFTMAX_XENT, s, C, sizeof(T) == 2 ? GCN_BF16 : GCN_F32, nr, 0, by4, by4, 0.0);
     switch (lpr4) {
-      case 1: k_softmax_xent_v4<T, 1><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-      case 2: k_softmax_xent_v4<T, 2><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-      case 4: k_softmax_xent_v4<T, 4><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-      case 8: k_softmax_xent_v4<T, 8><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-      case 16: k_softmax_xent_v4<T, 16><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-      case 32: k_softmax_xent_v4<T, 32><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-      default: k_softmax_xent_v4<T, 64><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      case 1: k_softmax_xent_v4<T, 1><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+      case 2: k_softmax_xent_v4<T, 2><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+      case 4: k_softmax_xent_v4<T, 4><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+      case 8: k_softmax_xent_v4<T, 8><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+      case 16: k_softmax_xent_v4<T, 16><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+      case 32: k_softmax_xent_v4<T, 32><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+      default: k_softmax_xent_v4<T, 64><<<nb4, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
     }
-    k_loss_finish<<<1, 256, 0, s>>>(nb4, scale, loss);
+    k_loss_finish<<<1, 256, 0, s>>>(nb4, scale, loss, slot);
     GCN_CHECK_LAUNCH();
     return GCN_OK;
   }
@@ -360,13 +366,13 @@ static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* 
     const double bys = (double)nr * (2.0 * sizeof(T) * C + 4.0);
     ProfScope ps(GCN_K_SOFTMAX_XENT, s, C, sizeof(T) == 2 ? GCN_BF16 : GCN_F32, nr, 0, bys, bys, 0.0);
     switch (lp) {
-      case 4: k_softmax_xent_s4<T, 4><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-      case 8: k_softmax_xent_s4<T, 8><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-      case 16: k_softmax_xent_s4<T, 16><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-      case 32: k_softmax_xent_s4<T, 32><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-      default: k_softmax_xent_s4<T, 64><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+      case 4: k_softmax_xent_s4<T, 4><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+      case 8: k_softmax_xent_s4<T, 8><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+      case 16: k_softmax_xent_s4<T, 16><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+      case 32: k_softmax_xent_s4<T, 32><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+      default: k_softmax_xent_s4<T, 64><<<nbs, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
     }
-    k_loss_finish<<<1, 256, 0, s>>>(nbs, scale, loss);
+    k_loss_finish<<<1, 256, 0, s>>>(nbs, scale, loss, slot);
     GCN_CHECK_LAUNCH();
     return GCN_OK;
   }
@@ -377,13 +383,13 @@ static int softmax_t(const T* Z, int64_t ldz, int64_t nr, int C, const int32_t* 
   const double by = (double)nr * (2.0 * sizeof(T) * C + 4.0);
   ProfScope ps(GCN_K_SOFTMAX_XENT, s, C, sizeof(T) == 2 ? GCN_BF16 : GCN_F32, nr, 0, by, by, 0.0);
   switch (lpr) {
-    case 4: k_softmax_xent<T, 4><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-    case 8: k_softmax_xent<T, 8><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-    case 16: k_softmax_xent<T, 16><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-    case 32: k_softmax_xent<T, 32><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
-    default: k_softmax_xent<T, 64><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg); break;
+    case 4: k_softmax_xent<T, 4><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+    case 8: k_softmax_xent<T, 8><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+    case 16: k_softmax_xent<T, 16><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+    case 32: k_softmax_xent<T, 32><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
+    default: k_softmax_xent<T, 64><<<nb, 256, 0, s>>>(Z, ldz, nr, C, y, scale, G, ldg, slot); break;
   }
-  k_loss_finish<<<1, 256, 0, s>>>(nb, scale, loss);
+  k_loss_finish<<<1, 256, 0, s>>>(nb, scale, loss, slot);
   GCN_CHECK_LAUNCH();
   return GCN_OK;
 }

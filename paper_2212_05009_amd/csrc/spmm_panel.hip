@@ -520,7 +520,7 @@ int bits_for_count(int64_t n) { int b = 1; while ((1LL << b) < n) ++b; return b;
 
 // Builds the layout for products with `ns` feature slices, `sw` accumulator floats per virtual
 // row and lane groups of `lpg` lanes.  *out stays null when the matrix does not fit the format.
-int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shift, hipStream_t s, PanelPlan** out) {
+static int build_plan_impl(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shift, hipStream_t s, PanelPlan** out) {
   *out = nullptr;
   const int64_t n = transposed ? A->nc : A->nr;
   const int64_t nnz = A->nnz;
@@ -696,6 +696,7 @@ int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shif
   GCN_HIP(hipStreamSynchronize(s));
   P->n_batches = n_batches;
   const int64_t n_ent = n_batches * epb * groups;
+  if (n_ent >= 0xffffff00LL) return GCN_OK;        // one thread per padded entry below: stay under 2^32 threads
   GCN_TRY(dev_alloc((void**)&P->ent, sizeof(uint2) * (size_t)n_ent));
   if (n_ent > 0) k_plan_fill_pad<<<(unsigned)ceil_div(n_ent, 256), 256, 0, s>>>(P->ent, n_ent);
   k_plan_scatter<<<grid, 256, 0, s>>>(sorted, spay, d_idx, d_val, nnz, kLidBits + cbbits, groups, epb, oseg.as<int64_t>(), P->wb, P->ent);
@@ -711,6 +712,16 @@ int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shif
 }
 
 }  // namespace
+
+// The host side works with std::vector; nothing may throw through the C boundary.
+int build_plan(gcn_csr* A, bool transposed, int ns, int sw, int lpg, int cb_shift, hipStream_t s, PanelPlan** out) {
+  try {
+    return build_plan_impl(A, transposed, ns, sw, lpg, cb_shift, s, out);
+  } catch (const std::bad_alloc&) {
+    *out = nullptr;
+    return fail(GCN_ENOMEM, "panel plan: host allocation failed");
+  }
+}
 
 void free_panel_plans(gcn_csr* A) {
   for (PanelPlan* p : A->plans) free_plan(p);
@@ -778,9 +789,21 @@ int spmm_panel_try(const SpmmArgs& a, hipStream_t s, bool* used) {
     if (p->transposed == a.transposed && p->ns == ns && p->sw == sw && p->lpg == lpg && p->cb_shift == cb_shift) { P = p; break; }
   if (!P) {
     GCN_TRY(build_plan(a.owner, a.transposed, ns, sw, lpg, cb_shift, s, &P));
-    if (!P) return GCN_OK;
-    a.owner->plans.push_back(P);
+    if (!P) {
+      // the matrix does not fit the packed format: remember that, so that later products of this shape fall back
+      // at once instead of repeating the host pass over the rows
+      P = new (std::nothrow) PanelPlan();
+      if (!P) return GCN_OK;
+      P->transposed = a.transposed; P->ns = ns; P->sw = sw; P->lpg = lpg; P->cb_shift = cb_shift; P->unusable = true;
+    }
+    try {
+      a.owner->plans.push_back(P);
+    } catch (const std::bad_alloc&) {
+      free_plan(P);
+      return fail(GCN_ENOMEM, "panel plan: host allocation failed");
+    }
   }
+  if (P->unusable) return GCN_OK;
 
   PanelK k{};                // (zeroes the fields of the embedded SpmmK that this kernel does not use)
   k.k.X = a.X; k.k.ldx = a.ldx; k.k.Y = a.Y; k.k.ldy = a.ldy; k.k.Y2 = a.Y2; k.k.ldy2 = a.ldy2;

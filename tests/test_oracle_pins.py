@@ -192,6 +192,30 @@ def test_halo_list_brute_force_and_partition_invariance(seed):
             assert np.all(np.diff(g.col[g.rowptr[i]:g.rowptr[i + 1]]) > 0)
 
 
+def test_block_takes_only_halo_degrees_from_the_global_array():
+    """D(i,i) is the row sum of A + I (Sec. 3.1) and a row block holds its rows whole (Sec. 4.1): the degrees of
+    owned vertices are counted, the global array only serves the halo vertices.  A block built with placeholders in
+    the owned positions must equal the block built with the whole graph's degrees, value for value, and both must
+    equal the rows of the dense definition."""
+    n, lo, hi = 40, 12, 29
+    src, dst = rand_edges(n, 150, 5)
+    whole = oracle.graph_build(src, dst, n)
+    Ad, _, _ = dense_norm_adj(src, dst, n)
+    marked = whole.deg.copy(); marked[lo:hi] = 1
+    a = oracle.graph_build(src, dst, n, lo, hi, deg_global=whole.deg)
+    b = oracle.graph_build(src, dst, n, lo, hi, deg_global=marked)
+    assert np.array_equal(a.val.view(np.int32), b.val.view(np.int32)) and np.array_equal(a.val64, b.val64)
+    assert np.array_equal(b.deg, whole.deg[lo:hi])
+    gid = np.concatenate([np.arange(lo, hi), b.halo_gid])
+    for i in range(b.nr):
+        for k in range(b.rowptr[i], b.rowptr[i + 1]):
+            assert abs(b.val64[k] - Ad[lo + i, gid[b.col[k]]]) <= 1e-15
+    # a wrong halo degree, on the other hand, must show
+    wrong = marked.copy(); wrong[b.halo_gid[0]] += 3
+    c = oracle.graph_build(src, dst, n, lo, hi, deg_global=wrong)
+    assert not np.array_equal(c.val64, b.val64)
+
+
 def test_graph_build_rejects_bad_input():
     with pytest.raises(ValueError):
         oracle.graph_build([0, 5], [1, 2], 4)

@@ -76,17 +76,15 @@ def row_block(n_global: int = 1 << 25, n_rows: int = 1 << 22, n_halo: int = 6 <<
               dims=(128, 128, 32), seed: int = BASE_SEED + 5):
     """Config 5: one processor's row block of a much larger power-law graph (owned rows + halo columns).
 
-    Extra keys: row_lo, row_hi, deg_global (int32 [n]: entries of each vertex's row of A + I; exact for the
-    owned rows, drawn from the same row-length law for the halo vertices, 1 elsewhere), table_seed (the
+    Extra keys: row_lo, row_hi, deg_global (int32 [n]: entries of each halo vertex's row of A + I, drawn from the
+    same row-length law as the owned rows; 1 everywhere else, the owned vertices included), table_seed (the
     feature table is workloads.table: every row recomputable).  y has one label per owned row; no X.
     """
     row_lo = (n_global // 4 // 64) * 64
     src, dst, halo_ids = graphs.row_block(n_global, row_lo, n_rows, n_halo, avg_degree, 0.5, seed)
-    # exact degrees of the owned rows: distinct non-diagonal columns, plus the diagonal of I
-    off = src != dst
-    key = np.unique(((src[off].astype(np.int64) - row_lo) << 32) | dst[off].astype(np.int64))
+    # degrees of the halo vertices, whose rows other processors hold; owned vertices keep the placeholder 1 (the build
+    # counts their rows itself and never reads these entries)
     deg = np.ones(n_global, dtype=np.int32)
-    deg[row_lo: row_lo + n_rows] += np.bincount((key >> 32).astype(np.int64), minlength=n_rows).astype(np.int32)
     u = prng.uniform01(seed, 11, 0, n_halo)
     raw = np.minimum((1.0 - u) ** (-1.0 / 1.2), 1.0e5)
     deg[halo_ids] = np.maximum(2, np.floor(raw * (avg_degree - 1.0) / raw.mean() + 1.5)).astype(np.int32)
