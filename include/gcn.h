@@ -378,7 +378,7 @@ int gcn_debug_max_grid_x(int64_t blocks);
  * GCN_TUNE_DEFAULT restores the built-in default).  Names: GCN_SPMM_PANEL (0 never / 1 always use the column
  * sweep; default by heuristic, -1), GCN_PANEL_NARROW, GCN_PANEL_NOSYNC, GCN_PANEL_VERBOSE, GCN_SPMM_SLICES
  * (1, 2, 4, 8; 0 = by rule), GCN_SPMM_EPG, GCN_SPMM_WIDE, GCN_GEMM_DIRECT, GCN_GEMM_FAST, GCN_GEMM_TN_WIDE,
- * GCN_GEMM_BF16 (0 = that kernel family off), GCN_GEMM_TN_BLOCKS, GCN_GATHER_HOST_BLOCKS.  No override changes
+ * GCN_GEMM_BF16, GCN_GEMM_REGW (0 = that kernel family off), GCN_GEMM_TN_BLOCKS, GCN_GATHER_HOST_BLOCKS.  No override changes
  * what is computed.  Returns GCN_EINVAL for an unknown name or a value out of range.  Process-wide and not
  * thread-safe against calls in flight on other host threads. */
 #define GCN_TUNE_DEFAULT (-2147483647 - 1)

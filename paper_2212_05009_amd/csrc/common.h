@@ -41,7 +41,7 @@ struct Tuning {
   int spmm_slices = 0;          // feature slices of the row kernel (0: by rule)
   int spmm_epg = 0;             // entries per lane group before a row is shared by more groups (0: default)
   int spmm_wide = 0;            // 64-bit gather addresses even where 32 bits suffice
-  int gemm_direct = 1, gemm_fast = 1, gemm_tn_wide = 1, gemm_bf16 = 1;   // 0 switches a dense kernel family off
+  int gemm_direct = 1, gemm_fast = 1, gemm_tn_wide = 1, gemm_bf16 = 1, gemm_regw = 1;   // 0 switches a dense kernel family off
   int gemm_tn_blocks = 512;     // blocks the A^T B kernel aims for
   int gather_host_blocks = 32;  // workgroups of the host-table gather
 };
@@ -285,6 +285,10 @@ int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, in
 // streaming variants (gemm_direct.hip): the long operand goes from global memory straight into the
 // MFMA operand registers; nn_direct needs W to fit in LDS (gemm_nn_direct_ok)
 bool gemm_nn_direct_ok(int N, int K);
+// W held in registers as MFMA operands, A streamed past it (gemm_regw.hip): fp32, K <= 256, N a multiple of 64 up to 256
+bool gemm_nn_regw_ok(const void* A, int64_t lda, int64_t M, int N, int K, int dtype);
+int gemm_nn_regw(const void* A, int64_t lda, const float* W, int64_t ldw, void* C, int64_t ldc, int64_t M, int N, int K,
+                 const GemmEpilogue& epi, hipStream_t s);
 // bf16 features on the bf16 matrix pipe (gemm_bf16.hip): W rounded to bf16 in LDS, fp32 accumulation
 bool gemm_nn_bf16_ok(const void* A, int64_t lda, void* C, int64_t ldc, int64_t M, int N, int K, const GemmEpilogue& epi);
 // A^T B for bf16 operands on the bf16 matrix pipe: partial tiles per row split, as gemm_tn_direct_partials

@@ -184,6 +184,23 @@ def test_layer_bwd_hubs_and_directed_block(gcn, dev, hubs, directed_block):
         run_bwd(gcn, dev, directed_block, d_in, d_out, mask=False, saved_ah=True)
 
 
+# the kernel that keeps W in registers and streams 64-row tiles of the operand through LDS: every epilogue, a K with
+# and without a tail, 1 to 4 wavefronts per workgroup, row counts around a tile and beyond one tile per workgroup
+@pytest.mark.parametrize("rows", [1, 63, 64, 65, 129, 16385, 70001])
+@pytest.mark.parametrize("d_in,d_out", [(256, 256), (128, 256), (200, 192), (100, 256), (68, 64), (256, 128)])
+def test_register_resident_weight_kernel(gcn, dev, rows, d_in, d_out):
+    case = Case(gcn, dev, np.zeros(0, np.int32), np.zeros(0, np.int32), rows)          # A^ = I
+    gcn.gcn_debug_set_tuning("GCN_GEMM_REGW", 2)
+    try:
+        run_fwd(gcn, dev, case, d_in, d_out, bias=True, save_ah=True)
+        run_fwd(gcn, dev, case, d_in, d_out)
+        run_bwd(gcn, dev, case, d_in, d_out, saved_ah=True, dbias=True)
+        run_bwd(gcn, dev, case, d_in, d_out, mask=False)
+    finally:
+        gcn.gcn_debug_set_tuning("GCN_GEMM_REGW", None)
+        case.A.free()
+
+
 # ----------------------------------------------------------------------------- softmax cross-entropy
 @pytest.mark.parametrize("d_in,d_out", [(128, 41), (41, 128), (256, 47), (200, 130), (130, 200)])
 def test_layer_with_the_column_sweep(gcn, dev, er, hubs, directed_block, d_in, d_out):
