@@ -250,9 +250,9 @@ int gemm_nn(const void* A, int64_t lda, const float* B, int64_t ldb, void* C, in
   }
   // Wide weight matrices are held in registers, the operand rows streamed past them through LDS.  Measured on
   // 2.45 M rows (TFLOP/s, this kernel / the LDS-resident-W kernel or, for 256 x 256, the LDS-tiled one):
-  // 256 x 256: 123 / 89, 128 x 256: 108 / 74, 200 x 192: 70 / 66, 100 x 256: 74 / 75, 128 x 128 (two of the four
+  // 256 x 256: 123 / 89, 128 x 256: 108 / 74, 200 x 192: 70 / 66, 100 x 256 (13 steps of 8 k): see the profile, 128 x 128 (two of the four
   // SIMDs busy): 49 / 113.  GCN_GEMM_REGW=2 takes it wherever it applies (tests).
-  if (use_direct() && gemm_nn_regw_ok(A, lda, M, N, K, dtype) && ((N >= 192 && K >= 112) || tune().gemm_regw == 2)) {
+  if (use_direct() && gemm_nn_regw_ok(A, lda, M, N, K, dtype) && ((N >= 192 && K >= 96) || tune().gemm_regw == 2)) {
     const double nb = (double)es * (double)M * (K + N * (epi.C2 ? 2.0 : 1.0) + (epi.mask ? N : 0)) + 4.0 * (double)K * N;
     ProfScope ps(GCN_K_GEMM_NN, s, N, dtype, M, K, nb, nb, 2.0 * (double)M * N * K);
     return gemm_nn_regw(A, lda, B, ldb, C, ldc, M, N, K, epi, s);

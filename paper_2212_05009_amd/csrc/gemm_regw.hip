@@ -213,6 +213,7 @@ int gemm_nn_regw(const void* A, int64_t lda, const float* W, int64_t ldw, void* 
   const int64_t ntiles = ceil_div(M, 64);
   const unsigned blocks = (unsigned)(ntiles < cus ? ntiles : cus);
   const int ks = (int)ceil_div(K, 8);
+  if (ks <= 13) return regw_launch<13>(a, blocks, s);
   if (ks <= 16) return regw_launch<16>(a, blocks, s);
   if (ks <= 24) return regw_launch<24>(a, blocks, s);
   return regw_launch<32>(a, blocks, s);

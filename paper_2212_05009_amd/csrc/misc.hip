@@ -408,6 +408,27 @@ __global__ __launch_bounds__(256) void k_pad_rows(const char* __restrict__ src, 
   reinterpret_cast<U*>(dst + r * pitch_dst)[c] = v;
 }
 
+// The same with 16-byte units for rows whose length is no multiple of 16 bytes but whose pitch is: the last unit of a
+// row reads into the source row's padding (which exists for every row but the buffer's last, copied separately) and
+// keeps only its first tail_bytes bytes.
+__global__ __launch_bounds__(256) void k_pad_rows_tail(const char* __restrict__ src, int64_t pitch_src, char* __restrict__ dst,
+                                                       int64_t pitch_dst, int64_t rows, int units_row, int units_dst,
+                                                       int tail_bytes) {
+  const int64_t i = block_id() * blockDim.x + threadIdx.x;
+  if (i >= rows * units_dst) return;
+  const int64_t r = i / units_dst; const int c = (int)(i - r * units_dst);
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (c < units_row) {
+    v = reinterpret_cast<const uint4*>(src + r * pitch_src)[c];
+    if (c == units_row - 1) {
+      uint16_t* h = reinterpret_cast<uint16_t*>(&v);
+#pragma unroll
+      for (int b = 0; b < 8; ++b) if (2 * b >= tail_bytes) h[b] = 0;
+    }
+  }
+  reinterpret_cast<uint4*>(dst + r * pitch_dst)[c] = v;
+}
+
 // the same for 2-byte elements whose source rows are only 2-byte aligned (odd pitch): a thread reads two elements
 // and writes one 4-byte word of the destination, whose pitch is even
 __global__ __launch_bounds__(256) void k_pad_rows_pairs(const uint16_t* __restrict__ src, int64_t ld_src, uint32_t* __restrict__ dst,
@@ -427,14 +448,24 @@ int pad_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t
   int ub = 16;
   while (ub > es && !((ps % ub) == 0 && (pd % ub) == 0 && (len % ub) == 0 && ((uintptr_t)src % ub) == 0 &&
                       ((uintptr_t)dst % ub) == 0)) ub >>= 1;
-  const int units_row = (int)(len / ub), units_dst = (int)(pd / ub);
-  const int64_t n = rows * units_dst;
   const double by = (double)es * (double)rows * (double)(d + ld_dst);
   ProfScope ps_(GCN_K_OTHER, s, d, dtype, rows, 0, by, by, 0.0);
   const char* sp = (const char*)src; char* dp = (char*)dst;
+  const int64_t len16 = round_up(len, 16);
+  if (ub < 16 && rows > 1 && (ps % 16) == 0 && (pd % 16) == 0 && ((uintptr_t)src % 16) == 0 && ((uintptr_t)dst % 16) == 0 &&
+      len16 <= ps && len16 <= pd) {
+    // all rows but the last with 16-byte units (a unit may read the padding of its source row), the last row exactly
+    const int64_t n16 = (rows - 1) * (pd / 16);
+    k_pad_rows_tail<<<fold_grid(ceil_div(n16, 256)), 256, 0, s>>>(sp, ps, dp, pd, rows - 1, (int)(len16 / 16), (int)(pd / 16),
+                                                                 (int)(len % 16));
+    sp += (rows - 1) * ps; dp += (rows - 1) * pd;
+    rows = 1;
+  }
+  const int units_row = (int)(len / ub), units_dst = (int)(pd / ub);
+  const int64_t n = rows * units_dst;
   if (ub == 2 && (ld_dst % 2) == 0 && ((uintptr_t)dst % 4) == 0) {
     const int64_t words = ld_dst / 2;
-    k_pad_rows_pairs<<<fold_grid(ceil_div(rows * words, 256)), 256, 0, s>>>((const uint16_t*)src, ld_src, (uint32_t*)dst, words, rows, d);
+    k_pad_rows_pairs<<<fold_grid(ceil_div(rows * words, 256)), 256, 0, s>>>((const uint16_t*)sp, ld_src, (uint32_t*)dp, words, rows, d);
     GCN_CHECK_LAUNCH();
     return GCN_OK;
   }
