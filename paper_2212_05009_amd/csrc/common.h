@@ -42,6 +42,7 @@ struct Tuning {
   int spmm_epg = 0;             // entries per lane group before a row is shared by more groups (0: default)
   int spmm_wide = 0;            // 64-bit gather addresses even where 32 bits suffice
   int gemm_direct = 1, gemm_fast = 1, gemm_tn_wide = 1, gemm_bf16 = 1, gemm_regw = 1;   // 0 switches a dense kernel family off
+  int gemm_tn_lds = 1;          // A^T B with both operands streamed through LDS: 0 off, 1 for wide fp32 outputs, 2 wherever it fits
   int gemm_tn_blocks = 512;     // blocks the A^T B kernel aims for
   int gather_host_blocks = 32;  // workgroups of the host-table gather
 };
@@ -302,6 +303,11 @@ int gemm_nn_bf16(const void* A, int64_t lda, const float* W, int64_t ldw, void* 
                  const GemmEpilogue& epi, hipStream_t s);
 int gemm_nn_direct(const void* A, int64_t lda, const float* W, int64_t ldw, void* C, int64_t ldc, int64_t M, int N,
                    int K, int dtype, const GemmEpilogue& epi, hipStream_t s);
+// A^T B partial tiles with the output in registers and both operands streamed through LDS (wide fp32 operands)
+bool gemm_tn_lds_ok(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype);
+size_t gemm_tn_lds_ws_bytes(int64_t Kd, int M, int N);
+int gemm_tn_lds_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, float* partial,
+                         int* nsplit_out, hipStream_t s);
 size_t gemm_tn_direct_ws_bytes(int64_t Kd, int M, int N);
 int gemm_tn_direct_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype,
                             float* partial, int* nsplit_out, hipStream_t s);

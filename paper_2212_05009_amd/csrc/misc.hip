@@ -500,7 +500,8 @@ const TuneField kTuneFields[] = {
     {"GCN_SPMM_SLICES", &Tuning::spmm_slices, 0, 8},        {"GCN_SPMM_EPG", &Tuning::spmm_epg, 0, 1 << 20},
     {"GCN_SPMM_WIDE", &Tuning::spmm_wide, 0, 1},            {"GCN_GEMM_DIRECT", &Tuning::gemm_direct, 0, 1},
     {"GCN_GEMM_FAST", &Tuning::gemm_fast, 0, 1},            {"GCN_GEMM_TN_WIDE", &Tuning::gemm_tn_wide, 0, 1},
-    {"GCN_GEMM_BF16", &Tuning::gemm_bf16, 0, 1},            {"GCN_GEMM_REGW", &Tuning::gemm_regw, 0, 2},            {"GCN_GEMM_TN_BLOCKS", &Tuning::gemm_tn_blocks, 1, 1 << 16},
+    {"GCN_GEMM_BF16", &Tuning::gemm_bf16, 0, 1},            {"GCN_GEMM_REGW", &Tuning::gemm_regw, 0, 2},
+    {"GCN_GEMM_TN_LDS", &Tuning::gemm_tn_lds, 0, 2},        {"GCN_GEMM_TN_BLOCKS", &Tuning::gemm_tn_blocks, 1, 1 << 16},
     {"GCN_GATHER_HOST_BLOCKS", &Tuning::gather_host_blocks, 1, 4096},
 };
 Tuning& tuning_storage() {

@@ -201,6 +201,23 @@ def test_register_resident_weight_kernel(gcn, dev, rows, d_in, d_out):
         case.A.free()
 
 
+# dW = (A^ H)^T G with the output in registers and both operands streamed through LDS, forced on for every shape it
+# accepts: each tile count per wavefront and each wavefront grid, outputs wider than one 256 x 256 workgroup, ragged
+# widths, row counts around a 32-row chunk, one short last chunk, many splits of the sum
+@pytest.mark.parametrize("rows", [1, 33, 129, 4097, 70001])
+@pytest.mark.parametrize("d_in,d_out", [(256, 256), (100, 256), (256, 100), (128, 128), (64, 16), (32, 256), (256, 32),
+                                        (64, 252), (300, 44), (44, 300), (520, 260)])
+def test_weight_gradient_kernel_with_operands_through_lds(gcn, dev, rows, d_in, d_out):
+    case = Case(gcn, dev, np.zeros(0, np.int32), np.zeros(0, np.int32), rows)          # A^ = I
+    gcn.gcn_debug_set_tuning("GCN_GEMM_TN_LDS", 2)
+    try:
+        run_bwd(gcn, dev, case, d_in, d_out, want_dh=False, saved_ah=True, dbias=True)
+        run_bwd(gcn, dev, case, d_in, d_out, mask=False)
+    finally:
+        gcn.gcn_debug_set_tuning("GCN_GEMM_TN_LDS", None)
+        case.A.free()
+
+
 # ----------------------------------------------------------------------------- softmax cross-entropy
 @pytest.mark.parametrize("d_in,d_out", [(128, 41), (41, 128), (256, 47), (200, 130), (130, 200)])
 def test_layer_with_the_column_sweep(gcn, dev, er, hubs, directed_block, d_in, d_out):
