@@ -172,6 +172,13 @@ int gcn_halo_gather(const void* table, int64_t ld, int64_t n_table_rows, int d, 
  *            (A^ H) W and A^ H is stored here for the backward pass; otherwise the library
  *            picks the cheaper of (A^ H) W and A^ (H W).  Both are the same sum; only the
  *            rounding order differs.
+ * Streams: the result is ordered on `stream` like that of any other call.  On large blocks (fp32, from about 10^5
+ * rows) the call may run its dense product on a second stream that the handle owns (default priority, created on
+ * first use, destroyed by gcn_csr_free), beside the sparse product of the same call, which is then launched on ranges
+ * of rows with the dense product one range behind (Sec. 4.1's row-wise tasks are independent; Sec. 4.1 overlaps
+ * communication with the local product in the same way).  Events tie that stream to `stream` at both ends: nothing of
+ * the call is pending on it when work enqueued on `stream` after the call starts.  The results do not depend on it
+ * (gcn_debug_set_tuning "GCN_OVERLAP" 0 keeps everything on `stream`).
  */
 int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W,
                   const float* bias, int d_in, int d_out, int act, int dtype, void* Z, void* Hout,
@@ -194,6 +201,8 @@ int gcn_layer_fwd_ld(const gcn_csr_t* A, const void* H, int64_t ldh, const float
  *   AH_saved device [nr x d_in] from gcn_layer_fwd or NULL.
  *   G        device [nr x d_out] (ld = d_out): gradient w.r.t. this layer's Z.
  * Needs GCN_BUILD_CSC when dH is requested.
+ * Streams: as gcn_layer_fwd; here it is dW from AH_saved, which needs nothing of the call's sparse product, that
+ * runs beside it on the handle's second stream.
  */
 int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, const void* AH_saved,
                   const float* W, int d_in, int d_out, int dtype, const void* G,
@@ -378,7 +387,11 @@ int gcn_debug_max_grid_x(int64_t blocks);
  * GCN_TUNE_DEFAULT restores the built-in default).  Names: GCN_SPMM_PANEL (0 never / 1 always use the column
  * sweep; default by heuristic, -1), GCN_PANEL_NARROW, GCN_PANEL_NOSYNC, GCN_PANEL_VERBOSE, GCN_SPMM_SLICES
  * (1, 2, 4, 8; 0 = by rule), GCN_SPMM_EPG, GCN_SPMM_WIDE, GCN_GEMM_DIRECT, GCN_GEMM_FAST, GCN_GEMM_TN_WIDE,
- * GCN_GEMM_BF16, GCN_GEMM_REGW (0 = that kernel family off), GCN_GEMM_TN_BLOCKS, GCN_GATHER_HOST_BLOCKS.  No override changes
+ * GCN_GEMM_BF16, GCN_GEMM_REGW, GCN_GEMM_TN_LDS (0 = that kernel family off), GCN_GEMM_TN_BLOCKS, GCN_GEMM_REGW_BLOCKS,
+ * GCN_GEMM_TN_LDS_BLOCKS (workgroups of the kernels that take whole compute units), GCN_GATHER_HOST_BLOCKS, GCN_OVERLAP
+ * (dense products beside sparse ones on a second stream: 0 never, 1 on large inputs, 2 wherever possible),
+ * GCN_OVERLAP_CUS (compute units those dense kernels take), GCN_OVERLAP_CHUNKS (row ranges of the sparse product that
+ * a dense product follows: 0, 2, 4, 8).  No override changes
  * what is computed.  Returns GCN_EINVAL for an unknown name or a value out of range.  Process-wide and not
  * thread-safe against calls in flight on other host threads. */
 #define GCN_TUNE_DEFAULT (-2147483647 - 1)

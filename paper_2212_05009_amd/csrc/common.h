@@ -43,6 +43,11 @@ struct Tuning {
   int spmm_wide = 0;            // 64-bit gather addresses even where 32 bits suffice
   int gemm_direct = 1, gemm_fast = 1, gemm_tn_wide = 1, gemm_bf16 = 1, gemm_regw = 1;   // 0 switches a dense kernel family off
   int gemm_tn_lds = 1;          // A^T B with both operands streamed through LDS: 0 off, 1 for wide fp32 outputs, 2 wherever it fits
+  int gemm_regw_blocks = 0;     // workgroups of the register-resident-W kernel; 0 = one per compute unit
+  int gemm_tn_lds_blocks = 0;   // workgroups of the LDS-streamed A^T B kernel; 0 = one per compute unit
+  int overlap = 1;              // the weight gradient beside the sparse product of the same layer call: 0 never, 1 on large blocks, 2 wherever possible
+  int overlap_cus = 64;         // compute units the dense kernels take while the sparse product runs
+  int overlap_chunks = 4;       // row chunks of a sparse product that a dense product follows: 2, 4 or 8; 0: no such pipeline
   int gemm_tn_blocks = 512;     // blocks the A^T B kernel aims for
   int gather_host_blocks = 32;  // workgroups of the host-table gather
 };
@@ -138,6 +143,8 @@ template <typename T> __device__ __forceinline__ void store_one(T* p, float v) {
 constexpr int kHubRowNnz = 2048;
 constexpr int kHubChunkNnz = 1024;
 
+constexpr int kRowChunks = 8;      // row ranges a sparse product can be launched on separately (or on runs of them)
+
 struct Schedule {
   int32_t* wave_rows = nullptr;   // [n_wave_rows] rows handled one wavefront each
   int64_t n_wave_rows = 0;
@@ -149,6 +156,15 @@ struct Schedule {
   // host copy: rows of length class c (lengths in [2^(31-c), 2^(32-c)); class 32 = empty rows) are
   // wave_rows[class_begin[c] .. class_begin[c+1]); classes are stored longest first.
   int64_t class_begin[34] = {0};
+  // host copy: the same lists cut at kRowChunks row boundaries chunk_row[j] (multiples of 64 rows; within a class the
+  // rows ascend): rows of class c in [chunk_row[j], chunk_row[j+1]) are wave_rows[chunk_class_begin[j][c] ..
+  // chunk_class_begin[j+1][c]); the hub rows (ascending too) of that range are hub_rows[chunk_hub_begin[j] ..
+  // chunk_hub_begin[j+1]), their chunks of entries chunk_hubchunk_begin[j] .. chunk_hubchunk_begin[j+1].  A product
+  // launched on one range of rows can be followed by dense work on those rows while the next range is multiplied.
+  int64_t chunk_row[kRowChunks + 1] = {0};
+  int64_t chunk_class_begin[kRowChunks + 1][33] = {{0}};
+  int64_t chunk_hub_begin[kRowChunks + 1] = {0};
+  int64_t chunk_hubchunk_begin[kRowChunks + 1] = {0};
 };
 
 // ---- panel plan: the column-sweep execution layout of a sparse matrix (spmm_panel.hip) -------
@@ -207,6 +223,11 @@ struct gcn_csr {
   void* ws = nullptr;      // scratch workspace, grown on demand
   size_t ws_bytes = 0;
   std::vector<gcn::PanelPlan*> plans;   // column-sweep layouts, built on first use (spmm_panel.hip)
+  // A second stream of the library's own (default priority, created on first use) for dense work that runs beside
+  // a sparse product of the same layer call, and the two events that order it against the caller's stream (one per
+  // hand-over to the side stream, one for the way back).
+  hipStream_t side_stream = nullptr;
+  hipEvent_t side_events[gcn::kRowChunks + 2] = {};
 };
 
 namespace gcn {
@@ -254,6 +275,9 @@ struct SpmmArgs {
   const int64_t* mid = nullptr;
   gcn_csr* owner = nullptr;  // handle the arrays belong to (lets the launch cache a panel plan); may be null
   bool no_alloc = false;     // the launch must not allocate: no column-sweep plan is built
+  // row_chunk >= 0: only the rows [sched->chunk_row[row_chunk], sched->chunk_row[row_chunk + row_chunk_n)) (never
+  // through the column sweep)
+  int row_chunk = -1, row_chunk_n = 1;
 };
 // ws: workspace for hub partial sums, at least spmm_ws_bytes(sched, d)
 size_t spmm_ws_bytes(const Schedule* sc, int d);
@@ -274,15 +298,21 @@ struct GemmEpilogue {
   int64_t ldmask = 0, mask_rows = 0;
   void* C2 = nullptr;            // optional second output: value before ReLU
   int64_t ldc2 = 0;
+  int max_blocks = 0;            // > 0: a kernel with one workgroup per compute unit launches at most this many
 };
+// true when gemm_nn runs this product on the kernel that occupies whole compute units, one workgroup each, and
+// therefore honours GemmEpilogue::max_blocks (the rest of the chip is left to a kernel on another stream)
+bool gemm_nn_limits_blocks(const void* A, int64_t lda, int64_t M, int N, int K, int dtype);
 // C[M x N] = A[M x K] * B[K x N];  A, C (and C2, mask) have element type dtype, B is f32.
 int gemm_nn(const void* A, int64_t lda, const float* B, int64_t ldb, void* C, int64_t ldc,
             int64_t M, int N, int K, int dtype, const GemmEpilogue& epi, hipStream_t s);
 // C[M x N] (f32) = A[Kdim x M]^T * B[Kdim x N], Kdim huge: split over blocks, partial tiles in ws
 // (gemm_tn_ws_bytes), then summed in a fixed order.  A, B element type dtype.
 size_t gemm_tn_ws_bytes(int64_t Kdim, int M, int N);
+// max_blocks > 0: as GemmEpilogue::max_blocks, honoured when gemm_tn_limits_blocks says so
+bool gemm_tn_limits_blocks(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kdim, int M, int N, int dtype);
 int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc,
-            int64_t Kdim, int M, int N, int dtype, void* ws, hipStream_t s);
+            int64_t Kdim, int M, int N, int dtype, void* ws, hipStream_t s, int max_blocks = 0);
 // streaming variants (gemm_direct.hip): the long operand goes from global memory straight into the
 // MFMA operand registers; nn_direct needs W to fit in LDS (gemm_nn_direct_ok)
 bool gemm_nn_direct_ok(int N, int K);
@@ -307,10 +337,13 @@ int gemm_nn_direct(const void* A, int64_t lda, const float* W, int64_t ldw, void
 bool gemm_tn_lds_ok(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype);
 size_t gemm_tn_lds_ws_bytes(int64_t Kd, int M, int N);
 int gemm_tn_lds_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, float* partial,
-                         int* nsplit_out, hipStream_t s);
+                         int* nsplit_out, hipStream_t s, int max_blocks = 0);
 size_t gemm_tn_direct_ws_bytes(int64_t Kd, int M, int N);
 int gemm_tn_direct_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype,
-                            float* partial, int* nsplit_out, hipStream_t s);
+                            float* partial, int* nsplit_out, hipStream_t s, int max_blocks = 0);
+// Holds the stream back for about 30 us (one sleeping wavefront): gives a kernel that was just released on another
+// stream, and that needs whole compute units, time to be placed before this stream's next kernel fills the chip.
+int stream_pause(hipStream_t s);
 // dst[rows x ld_dst] = src[rows x d] (leading dimension ld_src), zero in the padding columns
 int pad_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int d, int dtype, hipStream_t s);
 // Wt[N x K] = W[K x N]^T (f32, small)

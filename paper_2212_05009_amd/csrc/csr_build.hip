@@ -211,6 +211,27 @@ __global__ void k_hub_lists(const uint32_t* __restrict__ hub_flag, const int64_t
   for (uint32_t c = 0; c < hub_chunks[i]; ++c) chunk_hub[c0 + c] = (int32_t)h;
 }
 
+// Row boundaries in the schedule's lists.  For boundary j (row bound[j]): out[j * 35 + c], c < 33, = first position
+// of class c (list positions cb[c] .. cb[c + 1], rows ascending) whose row is >= bound[j]; out[j * 35 + 33] = first
+// hub row (ascending list of n_hub rows) >= bound[j]; out[j * 35 + 34] = that hub row's first chunk of entries.
+__global__ void k_chunk_bounds(const int32_t* __restrict__ wave_rows, const int64_t* __restrict__ cb,
+                               const int32_t* __restrict__ hub_rows, int64_t n_hub,
+                               const int64_t* __restrict__ hub_chunk_ptr, const int64_t* __restrict__ bound,
+                               int n_bounds, int64_t* __restrict__ out) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= n_bounds * 34) return;
+  const int j = t / 34, c = t % 34;
+  const int32_t* list = c < 33 ? wave_rows : hub_rows;
+  int64_t lo = c < 33 ? cb[c] : 0, hi = c < 33 ? cb[c + 1] : n_hub;
+  const int64_t r = bound[j];
+  while (lo < hi) {
+    const int64_t mid = lo + (hi - lo) / 2;
+    if ((int64_t)list[mid] < r) lo = mid + 1; else hi = mid;
+  }
+  out[j * 35 + c] = lo;
+  if (c == 33) out[j * 35 + 34] = hub_chunk_ptr[lo];
+}
+
 void free_schedule(Schedule* sc) {
   if (sc->wave_rows) (void)hipFree(sc->wave_rows);
   if (sc->hub_rows) (void)hipFree(sc->hub_rows);
@@ -266,7 +287,28 @@ int build_schedule(const int64_t* ptr, int64_t n, hipStream_t s, Schedule* out) 
                                                   hub_rows.as<int32_t>(), hub_chunk_ptr.as<int64_t>(),
                                                   chunk_hub.as<int32_t>());
   GCN_CHECK_LAUNCH();
+  // the class lists and the hub list cut at kRowChunks row boundaries (multiples of 64 rows)
+  DevBuf chunk_bound, chunk_cb;
+  constexpr int kChunkTable = (kRowChunks + 1) * 35;
+  GCN_TRY(chunk_bound.alloc(sizeof(int64_t) * (kRowChunks + 1)));
+  GCN_TRY(chunk_cb.alloc(sizeof(int64_t) * kChunkTable));
+  int64_t chunk_table[kChunkTable];
+  for (int j = 0; j <= kRowChunks; ++j) {
+    const int64_t r = round_up(ceil_div(n * j, kRowChunks), 64);
+    out->chunk_row[j] = j == kRowChunks || r > n ? n : r;
+  }
+  GCN_HIP(hipMemcpyAsync(chunk_bound.p, out->chunk_row, sizeof(int64_t) * (kRowChunks + 1), hipMemcpyHostToDevice, s));
+  k_chunk_bounds<<<(unsigned)ceil_div((kRowChunks + 1) * 34, 256), 256, 0, s>>>(
+      wave_rows.as<int32_t>(), class_begin.as<int64_t>(), hub_rows.as<int32_t>(), n_hub, hub_chunk_ptr.as<int64_t>(),
+      chunk_bound.as<int64_t>(), kRowChunks + 1, chunk_cb.as<int64_t>());
+  GCN_CHECK_LAUNCH();
+  GCN_HIP(hipMemcpyAsync(chunk_table, chunk_cb.p, sizeof(chunk_table), hipMemcpyDeviceToHost, s));
   GCN_HIP(hipStreamSynchronize(s));   // temporaries are freed on return
+  for (int j = 0; j <= kRowChunks; ++j) {
+    for (int c = 0; c < 33; ++c) out->chunk_class_begin[j][c] = chunk_table[j * 35 + c];
+    out->chunk_hub_begin[j] = chunk_table[j * 35 + 33];
+    out->chunk_hubchunk_begin[j] = chunk_table[j * 35 + 34];
+  }
   out->wave_rows = (int32_t*)wave_rows.release();
   out->n_wave_rows = n_wave;
   out->hub_rows = (int32_t*)hub_rows.release();
@@ -493,6 +535,8 @@ extern "C" int gcn_csr_free(gcn_csr_t* A) {
   free_schedule(&A->sched);
   free_schedule(&A->sched_t);
   free_panel_plans(A);
+  for (hipEvent_t e : A->side_events) if (e) (void)hipEventDestroy(e);
+  if (A->side_stream) (void)hipStreamDestroy(A->side_stream);
   delete A;
   return GCN_OK;
 }

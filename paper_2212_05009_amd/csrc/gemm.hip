@@ -239,6 +239,11 @@ static int gemm_nn_t(NnArgs& a, hipStream_t s) {
   return GCN_OK;
 }
 
+// fp32 only, so the bf16-pipe kernel never competes for these shapes
+bool gemm_nn_limits_blocks(const void* A, int64_t lda, int64_t M, int N, int K, int dtype) {
+  return use_direct() && gemm_nn_regw_ok(A, lda, M, N, K, dtype) && ((N >= 192 && K >= 96) || tune().gemm_regw == 2);
+}
+
 int gemm_nn(const void* A, int64_t lda, const float* B, int64_t ldb, void* C, int64_t ldc, int64_t M, int N,
             int K, int dtype, const GemmEpilogue& epi, hipStream_t s) {
   if (M == 0) return GCN_OK;
@@ -252,7 +257,7 @@ int gemm_nn(const void* A, int64_t lda, const float* B, int64_t ldb, void* C, in
   // 2.45 M rows (TFLOP/s, this kernel / the LDS-resident-W kernel or, for 256 x 256, the LDS-tiled one):
   // 256 x 256: 123 / 89, 128 x 256: 108 / 74, 200 x 192: 70 / 66, 100 x 256 (13 steps of 8 k): see the profile, 128 x 128 (two of the four
   // SIMDs busy): 49 / 113.  GCN_GEMM_REGW=2 takes it wherever it applies (tests).
-  if (use_direct() && gemm_nn_regw_ok(A, lda, M, N, K, dtype) && ((N >= 192 && K >= 96) || tune().gemm_regw == 2)) {
+  if (gemm_nn_limits_blocks(A, lda, M, N, K, dtype)) {
     const double nb = (double)es * (double)M * (K + N * (epi.C2 ? 2.0 : 1.0) + (epi.mask ? N : 0)) + 4.0 * (double)K * N;
     ProfScope ps(GCN_K_GEMM_NN, s, N, dtype, M, K, nb, nb, 2.0 * (double)M * N * K);
     return gemm_nn_regw(A, lda, B, ldb, C, ldc, M, N, K, epi, s);
@@ -443,14 +448,14 @@ size_t gemm_tn_ws_bytes(int64_t Kd, int M, int N) {
 }
 
 int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc, int64_t Kd, int M,
-            int N, int dtype, void* ws, hipStream_t s) {
+            int N, int dtype, void* ws, hipStream_t s, int max_blocks) {
   const size_t es = dtype == GCN_BF16 ? 2 : 4;
   const int64_t mn = (int64_t)M * N;
   int nsplit = 0;
   if (use_direct()) {
     const double nb = (double)es * (double)Kd * (M + N) + 4.0 * (double)mn;
     ProfScope ps(GCN_K_GEMM_TN, s, N, dtype, M, Kd, nb, nb, 2.0 * (double)Kd * M * N);
-    GCN_TRY(gemm_tn_direct_partials(A, lda, B, ldb, Kd, M, N, dtype, (float*)ws, &nsplit, s));
+    GCN_TRY(gemm_tn_direct_partials(A, lda, B, ldb, Kd, M, N, dtype, (float*)ws, &nsplit, s, max_blocks));
   } else {
     TnArgs a{A, lda, B, ldb, Kd, M, N, pick_vec(A, lda, M, es), pick_vec(B, ldb, N, es), 0, 0, (float*)ws};
     if (dtype == GCN_BF16) { if (a.vecA == 2) a.vecA = 1; if (a.vecB == 2) a.vecB = 1; }
@@ -478,6 +483,10 @@ int gemm_tn(const void* A, int64_t lda, const void* B, int64_t ldb, float* C, in
   }
   GCN_CHECK_LAUNCH();
   return GCN_OK;
+}
+
+bool gemm_tn_limits_blocks(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype) {
+  return use_direct() && !(dtype == GCN_BF16 && gemm_tn_bf16_ok(A, lda, B, ldb, Kd, M, N)) && gemm_tn_lds_ok(A, lda, B, ldb, Kd, M, N, dtype);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -799,10 +799,10 @@ size_t gemm_tn_direct_ws_bytes(int64_t Kd, int M, int N) {
 }
 
 int gemm_tn_direct_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype,
-                            float* partial, int* nsplit_out, hipStream_t s) {
+                            float* partial, int* nsplit_out, hipStream_t s, int max_blocks) {
   if (dtype == GCN_BF16 && gemm_tn_bf16_ok(A, lda, B, ldb, Kd, M, N))
     return gemm_tn_bf16_partials(A, lda, B, ldb, Kd, M, N, partial, nsplit_out, s);
-  if (gemm_tn_lds_ok(A, lda, B, ldb, Kd, M, N, dtype)) return gemm_tn_lds_partials(A, lda, B, ldb, Kd, M, N, partial, nsplit_out, s);
+  if (gemm_tn_lds_ok(A, lda, B, ldb, Kd, M, N, dtype)) return gemm_tn_lds_partials(A, lda, B, ldb, Kd, M, N, partial, nsplit_out, s, max_blocks);
   TnDirectArgs a{A, lda, B, ldb, Kd, M, N, 0, 0, partial};
   if (tn_wide_ok(A, lda, B, ldb, N, dtype)) {
     a.nsplit = tn_wide_splits(Kd, M, N);

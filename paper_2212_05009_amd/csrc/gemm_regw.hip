@@ -211,7 +211,9 @@ int gemm_nn_regw(const void* A, int64_t lda, const float* W, int64_t ldw, void* 
     return 256;
   }();
   const int64_t ntiles = ceil_div(M, 64);
-  const unsigned blocks = (unsigned)(ntiles < cus ? ntiles : cus);
+  int64_t lim = epi.max_blocks > 0 && epi.max_blocks < cus ? epi.max_blocks : cus;
+  if (tune().gemm_regw_blocks > 0 && tune().gemm_regw_blocks < lim) lim = tune().gemm_regw_blocks;
+  const unsigned blocks = (unsigned)(ntiles < lim ? ntiles : lim);
   const int ks = (int)ceil_div(K, 8);
   if (ks <= 13) return regw_launch<13>(a, blocks, s);
   if (ks <= 16) return regw_launch<16>(a, blocks, s);

@@ -179,7 +179,7 @@ bool gemm_tn_lds_ok(const void* A, int64_t lda, const void* B, int64_t ldb, int6
   return sh.tm * sh.tn >= 4 && M >= 64 && N >= 64;
 }
 
-static int tn_lds_splits(int64_t Kd, int M, int N) {
+static int tn_lds_splits(int64_t Kd, int M, int N, int max_blocks = 0) {
   static const int cus = [] {
     int dev = 0;
     hipDeviceProp_t p;
@@ -187,7 +187,10 @@ static int tn_lds_splits(int64_t Kd, int M, int N) {
       return p.multiProcessorCount;
     return 256;
   }();
-  int64_t want = cus / tn_lds_blocks_mn(M, N);         // one workgroup per compute unit (its LDS is taken whole)
+  // one workgroup per compute unit (its LDS is taken whole), or fewer: the rest is left to a concurrent kernel
+  int lim = tune().gemm_tn_lds_blocks > 0 && tune().gemm_tn_lds_blocks < cus ? tune().gemm_tn_lds_blocks : cus;
+  if (max_blocks > 0 && max_blocks < lim) lim = max_blocks;
+  int64_t want = lim / tn_lds_blocks_mn(M, N);
   const int64_t max_by_k = ceil_div(Kd, 4 * kTnlKC);
   if (want > max_by_k) want = max_by_k;
   return (int)(want < 1 ? 1 : want);
@@ -198,10 +201,10 @@ size_t gemm_tn_lds_ws_bytes(int64_t Kd, int M, int N) {
 }
 
 int gemm_tn_lds_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, float* partial,
-                         int* nsplit_out, hipStream_t s) {
+                         int* nsplit_out, hipStream_t s, int max_blocks) {
   TnLdsShape sh;
   if (!tn_lds_shape(M < 256 ? M : 256, N < 256 ? N : 256, &sh)) return fail(GCN_EINVAL, "gemm_tn_lds: shape");
-  const int want = tn_lds_splits(Kd, M, N);
+  const int want = tn_lds_splits(Kd, M, N, max_blocks);
   const int64_t rps = round_up(ceil_div(Kd, want), kTnlKC);
   const int nsplit = (int)ceil_div(Kd, rps);            // every split holds at least one row
   *nsplit_out = nsplit;

@@ -441,6 +441,18 @@ __global__ __launch_bounds__(256) void k_pad_rows_pairs(const uint16_t* __restri
   dst[i] = lo | (hi << 16);
 }
 
+// One wavefront that sleeps for a fixed number of rounds (about 30 us) and ends.
+__global__ void k_pause() {
+#pragma unroll 1
+  for (int i = 0; i < 8; ++i) __builtin_amdgcn_s_sleep(127);
+}
+
+int stream_pause(hipStream_t s) {
+  k_pause<<<1, 64, 0, s>>>();
+  GCN_CHECK_LAUNCH();
+  return GCN_OK;
+}
+
 int pad_rows(const void* src, int64_t ld_src, void* dst, int64_t ld_dst, int64_t rows, int d, int dtype, hipStream_t s) {
   if (rows <= 0) return GCN_OK;
   const int64_t es = dtype == GCN_BF16 ? 2 : 4;
@@ -502,7 +514,9 @@ const TuneField kTuneFields[] = {
     {"GCN_GEMM_FAST", &Tuning::gemm_fast, 0, 1},            {"GCN_GEMM_TN_WIDE", &Tuning::gemm_tn_wide, 0, 1},
     {"GCN_GEMM_BF16", &Tuning::gemm_bf16, 0, 1},            {"GCN_GEMM_REGW", &Tuning::gemm_regw, 0, 2},
     {"GCN_GEMM_TN_LDS", &Tuning::gemm_tn_lds, 0, 2},        {"GCN_GEMM_TN_BLOCKS", &Tuning::gemm_tn_blocks, 1, 1 << 16},
-    {"GCN_GATHER_HOST_BLOCKS", &Tuning::gather_host_blocks, 1, 4096},
+    {"GCN_GATHER_HOST_BLOCKS", &Tuning::gather_host_blocks, 1, 4096}, {"GCN_GEMM_TN_LDS_BLOCKS", &Tuning::gemm_tn_lds_blocks, 0, 4096}, {"GCN_GEMM_REGW_BLOCKS", &Tuning::gemm_regw_blocks, 0, 4096},
+    {"GCN_OVERLAP", &Tuning::overlap, 0, 2},               {"GCN_OVERLAP_CUS", &Tuning::overlap_cus, 1, 4096},
+    {"GCN_OVERLAP_CHUNKS", &Tuning::overlap_chunks, 0, 8},
 };
 Tuning& tuning_storage() {
   static Tuning t = [] {

@@ -78,8 +78,16 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
   k.bias = a.bias; k.Zprev = a.Zprev; k.ldz = a.ldz; k.n_mask_rows = a.n_mask_rows;
   k.partial = (float*)ws; k.d = a.d; k.epilogue = a.epilogue;
   if (a.n_rows == 0) return GCN_OK;
+  if (a.row_chunk >= 0 && (a.row_chunk_n < 1 || a.row_chunk + a.row_chunk_n > kRowChunks)) return fail(GCN_EINVAL, "spmm: no such row chunks");
+  const int rc1 = a.row_chunk + a.row_chunk_n;
+  if (a.row_chunk >= 0) {          // the long rows of this row range, and their chunks of entries
+    const Schedule* sc = a.sched;
+    k.chunk_lo = sc->chunk_hubchunk_begin[a.row_chunk]; k.n_chunks = sc->chunk_hubchunk_begin[rc1] - k.chunk_lo;
+    k.hub_lo = sc->chunk_hub_begin[a.row_chunk]; k.n_hub_rows = sc->chunk_hub_begin[rc1] - k.hub_lo;
+  }
   bool swept = false;
-  if (a.part == 0 && !a.no_alloc) GCN_TRY(spmm_panel_try(a, s, &swept));       // the column-sweep plan covers whole rows only
+  // the column-sweep plan covers whole rows of the whole matrix only
+  if (a.part == 0 && !a.no_alloc && a.row_chunk < 0) GCN_TRY(spmm_panel_try(a, s, &swept));
   if (swept) return GCN_OK;
   const size_t es = a.dtype == GCN_BF16 ? 2 : 4;
   // widest vector such that every feature-row load stays aligned (and inside the row's storage)
@@ -93,6 +101,14 @@ int spmm_launch(const SpmmArgs& a, void* ws, hipStream_t s) {
   pf.alg = csr + fe * (double)(a.n_cols + a.n_rows);
   pf.touched = csr + fe * (double)(a.nnz + a.n_rows);
   pf.flops = 2.0 * (double)a.nnz * a.d;
+  if (a.row_chunk >= 0) {            // a range of rows is charged its share of the rows (the host does not know its entry count)
+    const int64_t rows = a.sched->chunk_row[rc1] - a.sched->chunk_row[a.row_chunk];
+    const double share = (double)rows / (double)a.n_rows;
+    pf.alg *= share; pf.touched *= share; pf.flops *= share;
+    pf.rows = rows;
+    pf.nnz = (int64_t)((double)a.nnz * share);
+    pf.row_chunk = a.row_chunk; pf.row_chunk_n = a.row_chunk_n;
+  }
   // 32-bit addressing of X: row index and row pitch below 2^24, whole matrix below 4 GiB
   const double xspan = (double)a.n_cols * (double)a.ldx * (double)es;
   const bool narrow = a.n_cols < (1 << 24) && (double)a.ldx * (double)es < (double)(1 << 24) && xspan < 4294967296.0 &&

@@ -48,6 +48,7 @@ struct SpmmK {
   const int32_t* wave_rows;
   const int32_t* hub_rows; const int64_t* hub_chunk_ptr; const int32_t* chunk_hub; int64_t n_chunks;
   int64_t n_hub_rows;
+  int64_t chunk_lo, hub_lo;   // a launch on a range of rows: first chunk of entries and first hub row it covers (else 0)
   const void* X; int64_t ldx;
   void* Y; int64_t ldy;
   void* Y2; int64_t ldy2;
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
 
   if (item < a.n_chunks) {
     // ---- hub chunk: the whole block works on kHubChunkNnz entries of one long row
-    const int64_t c = item;
+    const int64_t c = a.chunk_lo + item;
     const int32_t h = a.chunk_hub[c];
     const int64_t row = a.hub_rows[h];
     const int64_t cs = a.ptr[row] + (c - a.hub_chunk_ptr[h]) * kHubChunkNnz;      // chunks are cut from the whole row
@@ -307,7 +308,7 @@ __global__ __launch_bounds__(256) void k_spmm_hub_finish(SpmmK a) {
   const int64_t tiles = (a.d + 63) / 64;
   const int64_t wi = block_id() * 4 + (threadIdx.x >> 6);
   if (wi >= a.n_hub_rows * tiles) return;
-  const int64_t h = wi / tiles;
+  const int64_t h = a.hub_lo + wi / tiles;
   const int64_t f = (wi % tiles) * 64 + lane;
   if (f >= a.d) return;
   const int64_t row = a.hub_rows[h];
@@ -326,7 +327,10 @@ __global__ __launch_bounds__(256) void k_spmm_hub_finish(SpmmK a) {
   finish_element<T>(a, row, f, v);
 }
 
-struct SpmmProf { int kind; int dtype; int64_t rows, nnz; double alg, touched, flops; };
+struct SpmmProf {
+  int kind; int dtype; int64_t rows, nnz; double alg, touched, flops;
+  int row_chunk = -1, row_chunk_n = 1;   // rows Schedule::chunk_row[row_chunk .. row_chunk + row_chunk_n); -1: all rows
+};
 
 // Entries each lane group should get before a row is shared by more groups (GCN_SPMM_EPG overrides, for
 // experiments).  Measured on an R-MAT graph with 45 entries per row: 4 / 8 / 16 / 32 / 64 entries per group
@@ -343,7 +347,9 @@ static int launch_l(SpmmK& k, const Schedule* sc, const SpmmProf& pf, bool narro
   k.n_bins = 0;
   int64_t waves = 0;
   for (int c = 0; c <= 32; ++c) {
-    const int64_t cnt = sc->class_begin[c + 1] - sc->class_begin[c];
+    const int64_t row_begin = pf.row_chunk < 0 ? sc->class_begin[c] : sc->chunk_class_begin[pf.row_chunk][c];
+    const int64_t row_end = pf.row_chunk < 0 ? sc->class_begin[c + 1] : sc->chunk_class_begin[pf.row_chunk + pf.row_chunk_n][c];
+    const int64_t cnt = row_end - row_begin;
     if (cnt <= 0) continue;
     const int64_t len_hi = c >= 32 ? 0 : ((int64_t)1 << (32 - c)) - 1;
     const int epg = tune().spmm_epg > 0 ? tune().spmm_epg : kEntriesPerGroup;
@@ -353,8 +359,8 @@ static int launch_l(SpmmK& k, const Schedule* sc, const SpmmProf& pf, bool narro
     int lg = 0; while ((1 << lg) < groups) ++lg;
     const int b = k.n_bins++;
     k.bin_wave_begin[b] = waves;
-    k.bin_row_begin[b] = sc->class_begin[c];
-    k.bin_row_end[b] = sc->class_begin[c + 1];
+    k.bin_row_begin[b] = row_begin;
+    k.bin_row_end[b] = row_end;
     k.bin_log2gr[b] = lg;
     waves += ceil_div(cnt, G >> lg);
   }

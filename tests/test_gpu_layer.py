@@ -218,6 +218,48 @@ def test_weight_gradient_kernel_with_operands_through_lds(gcn, dev, rows, d_in, 
         case.A.free()
 
 
+# The weight gradient from a saved A^ H beside the backward pass's sparse product (second stream), forced on for
+# small graphs: both orders of the backward products (d_out < d_in shares T = A^T G, otherwise Q = G W^T first), on a
+# whole graph, on one with long rows and on a directed row block.  Twice in a row: the stream, the events and the
+# workspace are reused; then once more without the saved A^ H, which takes the one-stream path again.
+@pytest.mark.parametrize("d_in,d_out", [(256, 256), (100, 256), (256, 100), (128, 192)])
+def test_weight_gradient_beside_the_sparse_product(gcn, dev, er, hubs, directed_block, d_in, d_out):
+    gcn.gcn_debug_set_tuning("GCN_OVERLAP", 2)
+    gcn.gcn_debug_set_tuning("GCN_GEMM_TN_LDS", 2)
+    try:
+        for case in (er, hubs, directed_block):
+            for rep in range(2):
+                run_bwd(gcn, dev, case, d_in, d_out, saved_ah=True, dbias=True, seed=rep)
+                run_bwd(gcn, dev, case, d_in, d_out, saved_ah=True, mask=False, seed=rep + 7)
+            run_bwd(gcn, dev, case, d_in, d_out, seed=3)
+    finally:
+        for name in ("GCN_OVERLAP", "GCN_GEMM_TN_LDS"):
+            gcn.gcn_debug_set_tuning(name, None)
+
+
+# The dense product of a sparse-first forward layer beside the sparse product (second stream), forced on for small
+# graphs: the sparse product is launched on 2, 4 or 8 ranges of rows, each with its share of the long rows, and the
+# dense product follows one range behind.  Graphs with fewer rows than ranges x 64 leave some ranges empty.
+@pytest.mark.parametrize("chunks", [2, 4, 8])
+@pytest.mark.parametrize("d_in,d_out", [(256, 256), (100, 256), (128, 192)])
+def test_forward_dense_product_follows_the_sparse_product_by_row_chunks(gcn, dev, er, hubs, directed_block, identity,
+                                                                        chunks, d_in, d_out):
+    gcn.gcn_debug_set_tuning("GCN_OVERLAP", 2)
+    gcn.gcn_debug_set_tuning("GCN_OVERLAP_CHUNKS", chunks)
+    gcn.gcn_debug_set_tuning("GCN_GEMM_REGW", 2)
+    try:
+        for case in (er, hubs, directed_block, identity):
+            for rep in range(2):
+                run_fwd(gcn, dev, case, d_in, d_out, bias=True, save_ah=True, seed=rep)
+            run_fwd(gcn, dev, case, d_in, d_out, want_z=False, act="none", seed=5)
+        tiny = Case(gcn, dev, np.array([0, 1, 2], np.int32), np.array([1, 2, 0], np.int32), 70)
+        run_fwd(gcn, dev, tiny, d_in, d_out, save_ah=True)
+        tiny.A.free()
+    finally:
+        for name in ("GCN_OVERLAP", "GCN_OVERLAP_CHUNKS", "GCN_GEMM_REGW"):
+            gcn.gcn_debug_set_tuning(name, None)
+
+
 # ----------------------------------------------------------------------------- softmax cross-entropy
 @pytest.mark.parametrize("d_in,d_out", [(128, 41), (41, 128), (256, 47), (200, 130), (130, 200)])
 def test_layer_with_the_column_sweep(gcn, dev, er, hubs, directed_block, d_in, d_out):
