@@ -288,6 +288,8 @@ def run_case(gcn, torch, name, dtype, steps, warmup, *, natural_ids=False, backw
     ep = Epoch(gcn, torch, A, X, Ws, y, bf16, table=table, overlap=overlap, backward=backward)
     del X
 
+    if calibrate_copy:            # a counter run keeps one stream throughout: its dispatches are attributed by order
+        gcn.gcn_debug_set_tuning("GCN_OVERLAP", 0)
     for _ in range(warmup):
         ep.run()
     torch.cuda.synchronize()
@@ -308,7 +310,7 @@ def run_case(gcn, torch, name, dtype, steps, warmup, *, natural_ids=False, backw
     recs, dropped = gcn.gcn_profile_records()
     kernels = summarise(recs, bsteps)
     dom0 = kernels[0]
-    if not calibrate_copy:        # (a counter run keeps one stream throughout: its dispatches are attributed by order)
+    if not calibrate_copy:
         gcn.gcn_debug_set_tuning("GCN_OVERLAP", None)
         ep.run()                  # the side stream and its events exist before the timed region
         torch.cuda.synchronize()
