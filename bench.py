@@ -241,7 +241,7 @@ def pick_block_global_rows():
 
 
 def run_case(gcn, torch, name, dtype, steps, warmup, *, natural_ids=False, backward="push", overlap=True,
-             calibrate_copy=False, w=None, keep_workload=False):
+             calibrate_copy=False, w=None, keep_workload=False, one_stream=False):
     """Generates (or reuses) a workload, builds the block, times `steps` epochs.  Returns (record, workload)."""
     import numpy as np
     from workloads import configs
@@ -288,7 +288,8 @@ def run_case(gcn, torch, name, dtype, steps, warmup, *, natural_ids=False, backw
     ep = Epoch(gcn, torch, A, X, Ws, y, bf16, table=table, overlap=overlap, backward=backward)
     del X
 
-    if calibrate_copy:            # a counter run keeps one stream throughout: its dispatches are attributed by order
+    one_stream = one_stream or calibrate_copy      # a counter run attributes its dispatches by order
+    if one_stream:
         gcn.gcn_debug_set_tuning("GCN_OVERLAP", 0)
     for _ in range(warmup):
         ep.run()
@@ -310,7 +311,7 @@ def run_case(gcn, torch, name, dtype, steps, warmup, *, natural_ids=False, backw
     recs, dropped = gcn.gcn_profile_records()
     kernels = summarise(recs, bsteps)
     dom0 = kernels[0]
-    if not calibrate_copy:
+    if not one_stream:
         gcn.gcn_debug_set_tuning("GCN_OVERLAP", None)
         ep.run()                  # the side stream and its events exist before the timed region
         torch.cuda.synchronize()
@@ -422,7 +423,7 @@ def run_case(gcn, torch, name, dtype, steps, warmup, *, natural_ids=False, backw
            "launches_per_epoch": round(sum(k["launches_per_step"] for k in kernels), 1),
            "roofline": roof, "dense_roofline": dense_roof, "kernels": kernels,
            "kernels_from": f"a separate pass of {bsteps} epochs with every launch timed, all on one stream",
-           "dense_beside_sparse": "off (counter run)" if calibrate_copy else "library default (on for large inputs)",
+           "dense_beside_sparse": "off (--one-stream or a counter run)" if one_stream else "library default (on for large inputs)",
            "profile_records_dropped": dropped}
 
     if calibrate_copy:
@@ -488,6 +489,8 @@ def main():
     ap.add_argument("--no-overlap", action="store_true",
                     help="block workloads: fetch the halo rows before the layer instead of during its owned-column product")
     ap.add_argument("--cpu-sample-frac", type=float, default=None)
+    ap.add_argument("--one-stream", action="store_true",
+                    help="keep every kernel on the caller's stream (GCN_OVERLAP=0): no dense product beside a sparse one")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run two row copies of known size (for scaling hardware byte counters)")
     args = ap.parse_args()
@@ -506,7 +509,7 @@ def main():
                                            and not args.calibrate_copy) else "none")
 
     out, w = run_case(gcn, torch, args.workload, args.dtype, args.steps, args.warmup, natural_ids=args.natural_ids,
-                      backward=args.backward, overlap=not args.no_overlap, calibrate_copy=args.calibrate_copy,
+                      backward=args.backward, overlap=not args.no_overlap, calibrate_copy=args.calibrate_copy, one_stream=args.one_stream,
                       keep_workload=True)
     out["host_mem_total_GiB"] = host_mem_gib()
 
