@@ -185,7 +185,11 @@ int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W
                   void* AH_save, void* stream);
 /* The same layer (Sec. 3.1 first equation, Sec. 4.1) with a leading dimension for every feature buffer, so that a
  * layer's output can be written straight into a buffer with the pitch the next layer's sparse product gathers
- * best from (gcn_feature_ld): Z (ldz), Hout (ldo), AH_save (ldah), each >= its row width. */
+ * best from (gcn_feature_ld): Z (ldz), Hout (ldo), AH_save (ldah), each >= its row width.  For this call and
+ * gcn_layer_bwd_ld a buffer whose leading dimension exceeds its row width must be backed by memory to the end of
+ * EVERY row's pitch, the last row included (rows x ld elements, as gcn_feature_ld's users allocate): the kernels may
+ * read the padding of an input row (whatever it holds, NaN included, reaches no result) and may write the padding of
+ * an output row up to the next multiple of 16 bytes of the row width (content unspecified). */
 int gcn_layer_fwd_ld(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W, const float* bias, int d_in,
                      int d_out, int act, int dtype, void* Z, int64_t ldz, void* Hout, int64_t ldo, void* AH_save,
                      int64_t ldah, void* stream);
@@ -208,7 +212,8 @@ int gcn_layer_bwd(const gcn_csr_t* A, const void* H, int64_t ldh, const void* AH
                   const float* W, int d_in, int d_out, int dtype, const void* G,
                   const void* Zprev, float* dW, float* dbias, void* dH, void* stream);
 /* The same backward pass (Sec. 3.1 second and third equations, Sec. 4.2) with a leading dimension for every
- * feature buffer: AH_saved (ldah), G (ldg), Zprev (ldzp), dH (lddh), each >= its row width. */
+ * feature buffer: AH_saved (ldah), G (ldg), Zprev (ldzp), dH (lddh), each >= its row width and, where larger, backed
+ * to the end of every row as stated for gcn_layer_fwd_ld. */
 int gcn_layer_bwd_ld(const gcn_csr_t* A, const void* H, int64_t ldh, const void* AH_saved, int64_t ldah,
                      const float* W, int d_in, int d_out, int dtype, const void* G, int64_t ldg, const void* Zprev,
                      int64_t ldzp, float* dW, float* dbias, void* dH, int64_t lddh, void* stream);

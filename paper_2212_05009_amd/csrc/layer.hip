@@ -274,17 +274,19 @@ extern "C" int gcn_layer_bwd_ld(const gcn_csr_t* A, const void* H, int64_t ldh, 
       // sparse product then gathers with vector loads
       // a caller's G that the sparse product cannot gather with 16-byte requests, or only across more lines than
       // need be, is first copied to a padded buffer
-      const bool g_unaligned = (ldg * (int64_t)es) % 16 != 0 || ((uintptr_t)G % 16) != 0 || (d_out * (int64_t)es) % 16 != 0;
+      // (a pitched G is backed to the end of every row, the last included: the contract of the _ld entry points; so a
+      // row that is no whole number of 16-byte vectors can still be gathered with them when the pitch leaves room)
+      const bool g_rows_backed = ldg >= round_up(d_out, 16 / (int64_t)es);
+      const bool g_unaligned = (ldg * (int64_t)es) % 16 != 0 || ((uintptr_t)G % 16) != 0 ||
+                               ((d_out * (int64_t)es) % 16 != 0 && !g_rows_backed);
       const int64_t ldgp = g_unaligned ? gather_ld_for(A, true, d_out, dtype) : padded_operand_ld(A, true, d_out, dtype, ldg);
-      // (rows that are no whole number of 16-byte vectors are copied even when the pitch is already right: only the
-      // library's own buffer is known to be backed up to the end of its last row)
       const bool pad_g = g_unaligned || ldgp != ldg;
       void* Gp = pad_g ? ws.take((size_t)A->nr * ldgp * es) : nullptr;
       if (pass) {
         if (pad_g) GCN_TRY(pad_rows(G, ldg, Gp, ldgp, A->nr, d_out, dtype, s));
         SpmmArgs sp{A->colptr, A->rowidx, A->val_t, &A->sched_t, A->nc, A->nr, A->nnz, true, A->nr, pad_g ? Gp : G,
                     pad_g ? ldgp : ldg, T, ldt, nullptr, 0, d_out, dtype, GCN_EPI_NONE, nullptr, nullptr, 0};
-        sp.x_rows_padded = pad_g;
+        sp.x_rows_padded = pad_g || g_rows_backed;
         sp.owner = Am;
         // dW from a saved A^ H needs nothing of this product: it runs beside it
         SideStream side;

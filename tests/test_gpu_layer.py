@@ -260,6 +260,53 @@ def test_forward_dense_product_follows_the_sparse_product_by_row_chunks(gcn, dev
             gcn.gcn_debug_set_tuning(name, None)
 
 
+# The layer calls with a leading dimension per buffer: every feature buffer a view of a wider allocation
+# (gcn_feature_ld's pitch) whose padding holds NaN: nothing of it may reach a result, and an output's padding is
+# written at most up to the next multiple of 16 bytes of the row width.
+@pytest.mark.parametrize("d_in,d_out", [(100, 47), (47, 100), (128, 41), (256, 256)])
+def test_layer_calls_with_pitched_buffers(gcn, dev, er, directed_block, d_in, d_out):
+    import torch
+
+    def pitched(a, rows, d):
+        buf = gcn.feature_buffer(rows, d, torch.float32, dev)
+        base = buf._base if buf._base is not None else buf
+        base.fill_(float("nan"))
+        if a is not None:
+            buf.copy_(torch.from_numpy(np.ascontiguousarray(a)).to(dev))
+        return buf, base
+
+    for case in (er, directed_block):
+        og, A = case.og, case.A
+        H, W, G, Zp, b = _inputs(og, d_in, d_out, False, 5 * d_in + d_out)
+        ref = oracle.layer_fwd(og, H, W, bias=b, act="relu")
+        Hd, _ = pitched(H, og.nc, d_in)
+        Hout, Hout_base = pitched(None, og.nr, d_out)
+        Z, _ = pitched(None, og.nr, d_out)
+        AH, _ = pitched(None, og.nr, d_in)
+        say(f"layer_fwd_ld nr={og.nr} nc={og.nc} {d_in}->{d_out}")
+        gcn.gcn_layer_fwd_ld(A, Hd, to_dev(W, dev), Hout, act=gcn.ACT_RELU, bias=to_dev(b, dev), Z=Z, AH_save=AH)
+        torch.cuda.synchronize()
+        check_bound(to_np(Hout), ref["Hout"], ref["Bz"], TOL_F32, "Hout")
+        check_bound(to_np(Z), ref["Z"], ref["Bz"], TOL_F32, "Z")
+        if Hout_base.shape[1] > (d_out + 3) // 4 * 4:
+            assert bool(torch.isnan(Hout_base[:, (d_out + 3) // 4 * 4:]).all()), "the padding of Hout was written past 16 bytes"
+        rb = oracle.layer_bwd(og, H, W, G, Zprev=Zp, want_dH=True, want_dbias=True)
+        Gd, _ = pitched(G, og.nr, d_out)
+        Zpd, _ = pitched(Zp, og.nr, d_in)
+        dH, dH_base = pitched(None, og.nc, d_in)
+        dW = torch.full((d_in, d_out), float("nan"), device=dev)
+        db = torch.full((d_out,), float("nan"), device=dev)
+        for saved in (AH, None):
+            say(f"layer_bwd_ld nr={og.nr} nc={og.nc} {d_in}->{d_out} saved_ah={saved is not None}")
+            gcn.gcn_layer_bwd_ld(A, Hd, to_dev(W, dev), Gd, dW, dH=dH, Zprev=Zpd, AH_saved=saved, dbias=db)
+            torch.cuda.synchronize()
+            check_bound(to_np(dW), rb["dW"], rb["BdW"], TOL_F32, "dW")
+            check_bound(to_np(dH), rb["dH"], rb["BdH"], TOL_F32, "dH")
+            check_bound(to_np(db), rb["dbias"], rb["Bdb"], TOL_F32, "dbias")
+        if dH_base.shape[1] > (d_in + 3) // 4 * 4:
+            assert bool(torch.isnan(dH_base[:, (d_in + 3) // 4 * 4:]).all()), "the padding of dH was written past 16 bytes"
+
+
 # ----------------------------------------------------------------------------- softmax cross-entropy
 @pytest.mark.parametrize("d_in,d_out", [(128, 41), (41, 128), (256, 47), (200, 130), (130, 200)])
 def test_layer_with_the_column_sweep(gcn, dev, er, hubs, directed_block, d_in, d_out):
