@@ -396,7 +396,7 @@ int gcn_debug_max_grid_x(int64_t blocks);
  * GCN_GEMM_TN_LDS_BLOCKS (workgroups of the kernels that take whole compute units), GCN_GATHER_HOST_BLOCKS, GCN_OVERLAP
  * (dense products beside sparse ones on a second stream: 0 never, 1 on large inputs, 2 wherever possible),
  * GCN_OVERLAP_CUS (compute units those dense kernels take), GCN_OVERLAP_CHUNKS (row ranges of the sparse product that
- * a dense product follows: 0, 2, 4, 8).  No override changes
+ * a dense product follows: 0, 2, 4, 8), GCN_PAUSE_ROUNDS (how long the caller's stream sleeps at a hand-over).  No override changes
  * what is computed.  Returns GCN_EINVAL for an unknown name or a value out of range.  Process-wide and not
  * thread-safe against calls in flight on other host threads. */
 #define GCN_TUNE_DEFAULT (-2147483647 - 1)

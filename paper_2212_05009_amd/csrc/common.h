@@ -47,6 +47,7 @@ struct Tuning {
   int gemm_tn_lds_blocks = 0;   // workgroups of the LDS-streamed A^T B kernel; 0 = one per compute unit
   int overlap = 1;              // the weight gradient beside the sparse product of the same layer call: 0 never, 1 on large blocks, 2 wherever possible
   int overlap_cus = 64;         // compute units the dense kernels take while the sparse product runs
+  int pause_rounds = 4;         // rounds of about 3.7 us that stream_pause sleeps (measured: 1 is too short, 2 is enough)
   int overlap_chunks = 4;       // row chunks of a sparse product that a dense product follows: 2, 4 or 8; 0: no such pipeline
   int gemm_tn_blocks = 512;     // blocks the A^T B kernel aims for
   int gather_host_blocks = 32;  // workgroups of the host-table gather
@@ -341,7 +342,7 @@ int gemm_tn_lds_partials(const void* A, int64_t lda, const void* B, int64_t ldb,
 size_t gemm_tn_direct_ws_bytes(int64_t Kd, int M, int N);
 int gemm_tn_direct_partials(const void* A, int64_t lda, const void* B, int64_t ldb, int64_t Kd, int M, int N, int dtype,
                             float* partial, int* nsplit_out, hipStream_t s, int max_blocks = 0);
-// Holds the stream back for about 30 us (one sleeping wavefront): gives a kernel that was just released on another
+// Holds the stream back for about 15 us (one sleeping wavefront): gives a kernel that was just released on another
 // stream, and that needs whole compute units, time to be placed before this stream's next kernel fills the chip.
 int stream_pause(hipStream_t s);
 // dst[rows x ld_dst] = src[rows x d] (leading dimension ld_src), zero in the padding columns

@@ -441,14 +441,14 @@ __global__ __launch_bounds__(256) void k_pad_rows_pairs(const uint16_t* __restri
   dst[i] = lo | (hi << 16);
 }
 
-// One wavefront that sleeps for a fixed number of rounds (about 30 us) and ends.
-__global__ void k_pause() {
+// One wavefront that sleeps for a fixed number of rounds (about 3.7 us each) and ends.
+__global__ void k_pause(int rounds) {
 #pragma unroll 1
-  for (int i = 0; i < 8; ++i) __builtin_amdgcn_s_sleep(127);
+  for (int i = 0; i < rounds; ++i) __builtin_amdgcn_s_sleep(127);
 }
 
 int stream_pause(hipStream_t s) {
-  k_pause<<<1, 64, 0, s>>>();
+  k_pause<<<1, 64, 0, s>>>(tune().pause_rounds);
   GCN_CHECK_LAUNCH();
   return GCN_OK;
 }
@@ -517,6 +517,7 @@ const TuneField kTuneFields[] = {
     {"GCN_GATHER_HOST_BLOCKS", &Tuning::gather_host_blocks, 1, 4096}, {"GCN_GEMM_TN_LDS_BLOCKS", &Tuning::gemm_tn_lds_blocks, 0, 4096}, {"GCN_GEMM_REGW_BLOCKS", &Tuning::gemm_regw_blocks, 0, 4096},
     {"GCN_OVERLAP", &Tuning::overlap, 0, 2},               {"GCN_OVERLAP_CUS", &Tuning::overlap_cus, 1, 4096},
     {"GCN_OVERLAP_CHUNKS", &Tuning::overlap_chunks, 0, 8},
+    {"GCN_PAUSE_ROUNDS", &Tuning::pause_rounds, 0, 64},
 };
 Tuning& tuning_storage() {
   static Tuning t = [] {
