@@ -98,6 +98,14 @@ static int64_t padded_operand_ld(const gcn_csr* A, bool transposed, int d, int d
 // needs the sparse product's result follows it row chunk by row chunk (Schedule::chunk_row), one chunk behind.
 struct SideStream {
   gcn_csr* A = nullptr; hipStream_t main = nullptr; hipStream_t side = nullptr;
+  bool open = false;       // forked and not yet joined
+  SideStream() = default;
+  SideStream(const SideStream&) = delete;
+  SideStream& operator=(const SideStream&) = delete;
+  // a call that fails between fork and join still leaves the caller's stream behind the side stream's work
+  ~SideStream() {
+    if (open && hipEventRecord(A->side_events[1], side) == hipSuccess) (void)hipStreamWaitEvent(main, A->side_events[1], 0);
+  }
   // what the caller's stream holds so far is done before anything enqueued on the side stream from here on
   int fork(gcn_csr* A_, hipStream_t main_) {
     A = A_; main = main_;
@@ -107,6 +115,7 @@ struct SideStream {
     side = A->side_stream;
     GCN_HIP(hipEventRecord(A->side_events[0], main));
     GCN_HIP(hipStreamWaitEvent(side, A->side_events[0], 0));
+    open = true;
     return GCN_OK;
   }
   // hand-over number `slot` (2 .. kRowChunks + 1): what the caller's stream holds so far is done before what the side
@@ -121,6 +130,7 @@ struct SideStream {
   }
   // the caller's stream goes on only when the side stream's work is done
   int join() {
+    open = false;
     GCN_HIP(hipEventRecord(A->side_events[1], side));
     GCN_HIP(hipStreamWaitEvent(main, A->side_events[1], 0));
     return GCN_OK;
