@@ -307,6 +307,38 @@ def test_layer_calls_with_pitched_buffers(gcn, dev, er, directed_block, d_in, d_
             assert bool(torch.isnan(dH_base[:, (d_in + 3) // 4 * 4:]).all()), "the padding of dH was written past 16 bytes"
 
 
+# Putting dense products beside sparse ones changes where kernels run, not what they add up: every result of a
+# layer call must be bit for bit the one that the same call gives with everything on the caller's stream.
+@pytest.mark.parametrize("d_in,d_out", [(256, 256), (100, 256)])
+def test_results_do_not_depend_on_the_second_stream(gcn, dev, hubs, directed_block, d_in, d_out):
+    import torch
+    for name, v in (("GCN_GEMM_REGW", 2), ("GCN_GEMM_TN_LDS", 2)):
+        gcn.gcn_debug_set_tuning(name, v)
+    try:
+        for case in (hubs, directed_block):
+            og, A = case.og, case.A
+            H, W, G, Zp, b = _inputs(og, d_in, d_out, False, 77)
+            Hd, Wd, Gd, Zpd, bd = to_dev(H, dev), to_dev(W, dev), to_dev(G, dev), to_dev(Zp, dev), to_dev(b, dev)
+            got = {}
+            for mode in (0, 2):
+                gcn.gcn_debug_set_tuning("GCN_OVERLAP", mode)
+                Hout = torch.empty(og.nr, d_out, device=dev); Z = torch.empty_like(Hout)
+                AH = torch.empty(og.nr, d_in, device=dev)
+                say(f"overlap={mode} layer_fwd nr={og.nr} {d_in}->{d_out}")
+                gcn.gcn_layer_fwd(A, Hd, Wd, Hout, act=gcn.ACT_RELU, bias=bd, Z=Z, AH_save=AH)
+                dW = torch.empty(d_in, d_out, device=dev)
+                dH = torch.empty(og.nc, d_in, device=dev)
+                say(f"overlap={mode} layer_bwd nr={og.nr} {d_in}->{d_out}")
+                gcn.gcn_layer_bwd(A, Hd, Wd, Gd, dW, dH=dH, Zprev=Zpd, AH_saved=AH)
+                torch.cuda.synchronize()
+                got[mode] = [to_np(t) for t in (Hout, Z, AH, dW, dH)]
+            for a, c, what in zip(got[0], got[2], ("Hout", "Z", "AH_save", "dW", "dH")):
+                assert np.array_equal(a, c), f"{what} differs between one stream and two"
+    finally:
+        for name in ("GCN_OVERLAP", "GCN_GEMM_REGW", "GCN_GEMM_TN_LDS"):
+            gcn.gcn_debug_set_tuning(name, None)
+
+
 # ----------------------------------------------------------------------------- softmax cross-entropy
 @pytest.mark.parametrize("d_in,d_out", [(128, 41), (41, 128), (256, 47), (200, 130), (130, 200)])
 def test_layer_with_the_column_sweep(gcn, dev, er, hubs, directed_block, d_in, d_out):
