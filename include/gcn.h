@@ -178,7 +178,9 @@ int gcn_halo_gather(const void* table, int64_t ld, int64_t n_table_rows, int d, 
  * of rows with the dense product one range behind (Sec. 4.1's row-wise tasks are independent; Sec. 4.1 overlaps
  * communication with the local product in the same way).  Events tie that stream to `stream` at both ends: nothing of
  * the call is pending on it when work enqueued on `stream` after the call starts.  The results do not depend on it
- * (gcn_debug_set_tuning "GCN_OVERLAP" 0 keeps everything on `stream`).
+ * (gcn_debug_set_tuning "GCN_OVERLAP" 0 keeps everything on `stream`).  Capture: once a first call has sized the
+ * workspace and created the second stream, the layer calls only enqueue kernels and event waits, and can be captured
+ * into a HIP graph through `stream` (the second stream joins the capture through its events).
  */
 int gcn_layer_fwd(const gcn_csr_t* A, const void* H, int64_t ldh, const float* W,
                   const float* bias, int d_in, int d_out, int act, int dtype, void* Z, void* Hout,
